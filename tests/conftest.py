@@ -1,0 +1,28 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session")
+def oracle_mod():
+    import oracle
+    oracle.build()
+    return oracle
+
+
+def pytest_sessionstart(session):
+    # The mutation test re-runs the pin suite in a child process against a deliberately broken
+    # build of the oracle source; the child finds that build through this variable.
+    path = os.environ.get("MLT_TEST_ORACLE_LIB")
+    if path:
+        import oracle
+        oracle.use_library(path)
