@@ -1,0 +1,112 @@
+/*
+ * mlt — tile-based dense kernels for AMD MI355X (gfx950, CDNA4, wave64), C ABI.
+ *
+ * The two operations are the dense workloads that arXiv 2503.14985 ("ML-Triton") lowers
+ * workgroup -> warp -> intrinsic: a 16-bit GEMM with 32-bit accumulation (Section 2, Listing 1)
+ * and a FlashAttention-2-style attention forward (Section 2.5, Algorithm 1). Here both are
+ * hand-written HIP kernels; the workgroup tile -> per-wavefront sub-tile -> MFMA tile split is
+ * fixed at compile time per kernel variant.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers to memory the caller owns. The library never frees
+ *     or keeps them. Inputs and outputs must not overlap.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Work is enqueued
+ *     asynchronously on it; no entry point synchronises the device.
+ *   - `dtype` selects the 16-bit element type of every input and output tensor:
+ *     MLT_BF16 (bfloat16) or MLT_FP16 (IEEE binary16). Accumulation is fp32; outputs are
+ *     rounded to `dtype` with round-to-nearest-even.
+ *   - Return value: MLT_OK or a negative mlt_status. No C++ exception crosses the boundary and
+ *     nothing aborts. On an error nothing has been enqueued.
+ */
+#ifndef MLT_H_
+#define MLT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MLT_BF16 = 0, MLT_FP16 = 1 } mlt_dtype;
+
+typedef enum {
+  MLT_OK = 0,
+  MLT_ERR_INVALID_ARG = -1, /* null pointer, negative size, leading dimension too small, bad dtype */
+  MLT_ERR_UNSUPPORTED = -2, /* valid request with no kernel (e.g. head dimension not 64 or 128) */
+  MLT_ERR_LAUNCH = -3,      /* the HIP runtime rejected the kernel launch */
+  MLT_ERR_DEVICE = -4       /* no usable gfx950 device is current */
+} mlt_status;
+
+/*
+ * GEMM, Section 2 of the paper (A is m x k, B is k x n, C is m x n; 16-bit inputs, fp32
+ * accumulate as in Listing 1). Computes C = A * B, overwriting C (no accumulation into the
+ * previous contents), output rounded to `dtype`.
+ *
+ *   A      device, M x K row-major, row stride lda >= K elements
+ *   B      device; transB == 0: K x N row-major, row stride ldb >= N
+ *                  transB != 0: the N x K row-major array holding B transposed (B in
+ *                               column-major order), row stride ldb >= K
+ *   C      device, M x N row-major, row stride ldc >= N; written, never read
+ *
+ * M, N or K may be 0: M == 0 or N == 0 is a no-op, K == 0 stores zeros. Any positive shape and
+ * any leading dimensions/alignments are accepted; shapes and pointers that allow 16-byte vector
+ * access (K, N, lda, ldb multiples of 8 and 16-byte aligned bases) take the fast kernels, others
+ * a slower general kernel with identical results up to summation order.
+ */
+int mlt_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+             int64_t ldb, int transB, void* C, int64_t ldc, int dtype, void* stream);
+
+/*
+ * Attention forward, Section 2.5 / Algorithm 1 of the paper, per batch b and head h:
+ *   O = softmax(scale * Q K^T  [+ causal mask]) V
+ * computed tile by tile with the online-softmax recurrence (running row maximum m and row sum
+ * l in fp32, P rounded to `dtype` before the second product, one division by l at the end).
+ *
+ *   Q, O   device, contiguous [B, H, Sq, D], D innermost
+ *   K, V   device, contiguous [B, H, Sk, D]
+ *   causal != 0: key j is visible to query i iff j <= i (lower triangle including the
+ *                diagonal, aligned at the top-left corner; key 0 is visible to every query).
+ *
+ * D must be 64 or 128 (else MLT_ERR_UNSUPPORTED). B, H or Sq equal to 0 is a no-op. Sk must be
+ * >= 1 (a softmax over no keys is undefined: MLT_ERR_INVALID_ARG). All four base pointers must
+ * be 16-byte aligned (MLT_ERR_INVALID_ARG otherwise).
+ */
+int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const void* Q,
+                const void* K, const void* V, void* O, float scale, int causal, int dtype,
+                void* stream);
+
+/*
+ * Per-kernel timing hook for benchmarks: when `start_event`/`stop_event` (hipEvent_t as void*,
+ * may be NULL) are set, the next launches made by this thread record them on the launch stream
+ * immediately before the first and after the last kernel of one entry-point call. Pass NULLs to
+ * switch it off. Host-side state only; thread-local.
+ */
+void mlt_set_timing_events(void* start_event, void* stop_event);
+
+/*
+ * Name of the kernel variant the last successful call on this thread selected (static string,
+ * e.g. "gemm_bf16_nn_256x256x64"); "" before any call. For logs and profiles.
+ */
+const char* mlt_last_kernel(void);
+
+/*
+ * Host-only query of the tiling a call would use, mirroring the paper's layout encoding
+ * (Section 2.1: sizePerWarp and warpsPerCTA of the root operation). Fills
+ *   out[0..1] workgroup tile (rows, cols), out[2..3] wavefronts per workgroup (rows, cols),
+ *   out[4..5] sub-tile per wavefront, out[6..8] MFMA tile (m, n, k), out[9] K step (GEMM) or key
+ *   tile (attention).
+ * `op` 0 = GEMM (dims = M, N, K, transB), 1 = attention (dims = Sq, Sk, D, causal).
+ * Returns MLT_OK or an error as the compute call would.
+ */
+int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]);
+
+/* Static, human-readable text for a status code. */
+const char* mlt_status_string(int status);
+
+/* Static version string, "major.minor.patch". */
+const char* mlt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MLT_H_ */

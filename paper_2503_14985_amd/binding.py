@@ -1,0 +1,157 @@
+"""ctypes binding of libmlt.so: the same names as the C ABI in include/mlt.h, argument marshalling
+only. Every step of both operations runs in the HIP kernels; there is no fallback: if the
+library has not been built, importing this module raises.
+
+Tensors are torch tensors on the GPU (bf16 or fp16); torch is used for device memory and the
+current stream, nothing else.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmlt.so")
+
+MLT_BF16, MLT_FP16 = 0, 1
+MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE = 0, -1, -2, -3, -4
+
+EXPORTS = ("mlt_gemm", "mlt_mha_fwd", "mlt_set_timing_events", "mlt_last_kernel",
+           "mlt_query_tiling", "mlt_status_string", "mlt_version")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libmlt.so is not built (%s). Run `python -c 'import __graft_entry__ as g; g.build()'` "
+        "from the repository root; there is no CPU fallback." % LIB_PATH)
+
+_lib = ctypes.CDLL(LIB_PATH)
+_i64, _p, _i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+_lib.mlt_gemm.restype = _i32
+_lib.mlt_gemm.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _p]
+_lib.mlt_mha_fwd.restype = _i32
+_lib.mlt_mha_fwd.argtypes = [_i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, ctypes.c_float, _i32,
+                             _i32, _p]
+_lib.mlt_set_timing_events.restype = None
+_lib.mlt_set_timing_events.argtypes = [_p, _p]
+_lib.mlt_last_kernel.restype = ctypes.c_char_p
+_lib.mlt_query_tiling.restype = _i32
+_lib.mlt_query_tiling.argtypes = [_i32, ctypes.POINTER(_i64), _i32, ctypes.POINTER(ctypes.c_int32)]
+_lib.mlt_status_string.restype = ctypes.c_char_p
+_lib.mlt_status_string.argtypes = [_i32]
+_lib.mlt_version.restype = ctypes.c_char_p
+
+
+class MltError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, mlt_status_string(status), status))
+
+
+def raw():
+    """The ctypes library object, for tests that pass raw pointers (error paths)."""
+    return _lib
+
+
+def mlt_status_string(status: int) -> str:
+    return _lib.mlt_status_string(status).decode()
+
+
+def mlt_version() -> str:
+    return _lib.mlt_version().decode()
+
+
+def mlt_last_kernel() -> str:
+    return _lib.mlt_last_kernel().decode()
+
+
+def mlt_query_tiling(op: int, dims, dtype: int):
+    d = (_i64 * 4)(*[int(x) for x in dims])
+    out = (ctypes.c_int32 * 10)()
+    rc = _lib.mlt_query_tiling(op, d, dtype, out)
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_query_tiling")
+    return list(out)
+
+
+def mlt_set_timing_events(start, stop) -> None:
+    """start/stop: raw hipEvent_t handles as ints (or None)."""
+    _lib.mlt_set_timing_events(start, stop)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return MLT_BF16
+    if t.dtype == torch.float16:
+        return MLT_FP16
+    raise TypeError("mlt works on bfloat16 / float16 tensors, got %s" % t.dtype)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _rows_contiguous(t: torch.Tensor, name: str) -> int:
+    if t.dim() != 2:
+        raise ValueError("%s must be 2-D" % name)
+    if t.shape[1] > 1 and t.stride(1) != 1:
+        raise ValueError("%s must have contiguous rows" % name)
+    return t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+
+
+def mlt_gemm(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor | None = None, transB: bool = False,
+             stream=None) -> torch.Tensor:
+    """C = A @ B (transB=False, B is [K, N]) or C = A @ B.T (transB=True, B is [N, K]).
+
+    Row strides of A, B and C are passed through as lda/ldb/ldc, so row-sliced views work."""
+    if not (A.is_cuda and B.is_cuda):
+        raise ValueError("mlt_gemm needs GPU tensors")
+    dt = _dtype_code(A)
+    if B.dtype != A.dtype:
+        raise TypeError("A and B must share a dtype")
+    M, K = A.shape
+    N, Kb = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
+    if K != Kb:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, Kb))
+    if C is None:
+        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    elif C.dtype != A.dtype or tuple(C.shape) != (M, N):
+        raise ValueError("C has the wrong dtype or shape")
+    lda, ldb, ldc = _rows_contiguous(A, "A"), _rows_contiguous(B, "B"), _rows_contiguous(C, "C")
+    with torch.cuda.device(A.device):
+        rc = _lib.mlt_gemm(M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, int(transB),
+                           C.data_ptr(), ldc, dt, _stream(stream))
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_gemm")
+    return C
+
+
+def mlt_mha_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, scale: float,
+                causal: bool = False, O: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """O = softmax(scale * Q K^T [+ causal mask]) V for contiguous [B, H, S, D] tensors."""
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda):
+        raise ValueError("mlt_mha_fwd needs GPU tensors")
+    dt = _dtype_code(Q)
+    if K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise TypeError("Q, K and V must share a dtype")
+    if Q.dim() != 4 or K.dim() != 4 or V.shape != K.shape:
+        raise ValueError("expected Q [B,H,Sq,D], K and V [B,H,Sk,D]")
+    B, H, Sq, D = Q.shape
+    Sk = K.shape[2]
+    if K.shape != (B, H, Sk, D):
+        raise ValueError("K shape does not match Q")
+    if not (Q.is_contiguous() and K.is_contiguous() and V.is_contiguous()):
+        raise ValueError("Q, K and V must be contiguous")
+    if O is None:
+        O = torch.empty_like(Q)
+    elif O.dtype != Q.dtype or O.shape != Q.shape or not O.is_contiguous():
+        raise ValueError("O has the wrong dtype, shape or layout")
+    with torch.cuda.device(Q.device):
+        rc = _lib.mlt_mha_fwd(B, H, Sq, Sk, D, Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                              O.data_ptr(), float(scale), int(causal), dt, _stream(stream))
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_mha_fwd")
+    return O

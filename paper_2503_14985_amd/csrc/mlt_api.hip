@@ -1,0 +1,169 @@
+// C ABI of the library: argument validation, variant selection, launch. No device work happens
+// here besides enqueueing kernels on the caller's stream.
+#include <limits.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "mlt_common.h"
+#include "mlt_internal.h"
+
+using namespace mlt;
+
+namespace {
+
+thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+thread_local const char* g_last_kernel = "";
+
+bool device_is_gfx950() {
+  static thread_local int cached_dev = -1;
+  static thread_local bool cached_ok = false;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return false; }
+  if (dev != cached_dev) {
+    hipDeviceProp_t p;
+    if (hipGetDeviceProperties(&p, dev) != hipSuccess) { (void)hipGetLastError(); return false; }
+    cached_ok = strncmp(p.gcnArchName, "gfx950", 6) == 0;
+    cached_dev = dev;
+  }
+  return cached_ok;
+}
+
+int forced_gemm_variant() {
+  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128.
+  const char* e = getenv("MLT_GEMM_VARIANT");
+  if (!e || !*e) return GEMM_AUTO;
+  if (!strcmp(e, "general")) return GEMM_GENERAL;
+  if (!strcmp(e, "256")) return GEMM_256;
+  if (!strcmp(e, "128")) return GEMM_128;
+  return GEMM_AUTO;
+}
+
+int check_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+               int64_t ldb, int transB, const void* C, int64_t ldc, int dtype) {
+  if (dtype != MLT_BF16 && dtype != MLT_FP16) return MLT_ERR_INVALID_ARG;
+  if (M < 0 || N < 0 || K < 0) return MLT_ERR_INVALID_ARG;
+  if (M > INT_MAX || N > INT_MAX || K > INT_MAX) return MLT_ERR_UNSUPPORTED;
+  if (M == 0 || N == 0) return MLT_OK;
+  if (!C || ldc < N) return MLT_ERR_INVALID_ARG;
+  if (K > 0) {
+    if (!A || !B) return MLT_ERR_INVALID_ARG;
+    if (lda < K) return MLT_ERR_INVALID_ARG;
+    if (ldb < (transB ? K : N)) return MLT_ERR_INVALID_ARG;
+  }
+  return MLT_OK;
+}
+
+int check_mha(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const void* Q,
+              const void* K, const void* V, const void* O, float scale, int dtype) {
+  if (dtype != MLT_BF16 && dtype != MLT_FP16) return MLT_ERR_INVALID_ARG;
+  if (B < 0 || H < 0 || Sq < 0 || Sk < 0 || D <= 0) return MLT_ERR_INVALID_ARG;
+  if (!(scale == scale)) return MLT_ERR_INVALID_ARG;     // NaN
+  if (D != 64 && D != 128) return MLT_ERR_UNSUPPORTED;
+  if (B == 0 || H == 0 || Sq == 0) return MLT_OK;
+  if (Sk < 1) return MLT_ERR_INVALID_ARG;
+  if (!Q || !K || !V || !O) return MLT_ERR_INVALID_ARG;
+  auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  if (!al16(Q) || !al16(K) || !al16(V) || !al16(O)) return MLT_ERR_INVALID_ARG;
+  if (Sq > INT_MAX || Sk > INT_MAX || B * H > INT_MAX) return MLT_ERR_UNSUPPORTED;
+  return MLT_OK;
+}
+
+struct TimedRegion {
+  hipStream_t s;
+  explicit TimedRegion(hipStream_t st) : s(st) { if (g_ev_start) (void)hipEventRecord(g_ev_start, s); }
+  ~TimedRegion() { if (g_ev_stop) (void)hipEventRecord(g_ev_stop, s); }
+};
+
+}  // namespace
+
+extern "C" {
+
+int mlt_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+             int64_t ldb, int transB, void* C, int64_t ldc, int dtype, void* stream) {
+  int rc = check_gemm(M, N, K, A, lda, B, ldb, transB, C, ldc, dtype);
+  if (rc != MLT_OK) return rc;
+  if (M == 0 || N == 0) return MLT_OK;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
+             (uint16_t*)C, ldc, dtype, forced_gemm_variant()};
+  GemmPlan p = plan_gemm(g);
+  hipStream_t s = (hipStream_t)stream;
+  {
+    TimedRegion t(s);
+    rc = run_gemm(g, p, s);
+  }
+  if (rc == MLT_OK) g_last_kernel = p.name;
+  return rc;
+}
+
+int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const void* Q,
+                const void* K, const void* V, void* O, float scale, int causal, int dtype,
+                void* stream) {
+  int rc = check_mha(B, H, Sq, Sk, D, Q, K, V, O, scale, dtype);
+  if (rc != MLT_OK) return rc;
+  if (B == 0 || H == 0 || Sq == 0) return MLT_OK;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  MhaArgs a{B, H, Sq, Sk, D, (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
+            (uint16_t*)O, scale, causal ? 1 : 0, dtype};
+  MhaPlan p = plan_mha(a);
+  if (!p.supported) return MLT_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    TimedRegion t(s);
+    rc = run_mha(a, p, s);
+  }
+  if (rc == MLT_OK) g_last_kernel = p.name;
+  return rc;
+}
+
+void mlt_set_timing_events(void* start_event, void* stop_event) {
+  g_ev_start = (hipEvent_t)start_event;
+  g_ev_stop = (hipEvent_t)stop_event;
+}
+
+const char* mlt_last_kernel(void) { return g_last_kernel; }
+
+int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]) {
+  if (!dims || !out) return MLT_ERR_INVALID_ARG;
+  if (dtype != MLT_BF16 && dtype != MLT_FP16) return MLT_ERR_INVALID_ARG;
+  if (op == 0) {
+    if (dims[0] < 0 || dims[1] < 0 || dims[2] < 0) return MLT_ERR_INVALID_ARG;
+    // Alignment is unknown here: assume aligned pointers and tight leading dimensions.
+    GemmArgs g{dims[0], dims[1], dims[2], nullptr, dims[2], nullptr, dims[3] ? dims[2] : dims[1],
+               dims[3] ? 1 : 0, nullptr, dims[1], dtype, forced_gemm_variant()};
+    GemmPlan p = plan_gemm(g);
+    if (p.variant == GEMM_ZERO) { for (int i = 0; i < 10; ++i) out[i] = 0; return MLT_OK; }
+    out[0] = p.bm; out[1] = p.bn; out[2] = p.wm; out[3] = p.wn;
+    out[4] = p.bm / p.wm; out[5] = p.bn / p.wn; out[6] = 32; out[7] = 32; out[8] = 16;
+    out[9] = p.bk;
+    return MLT_OK;
+  }
+  if (op == 1) {
+    if (dims[0] < 0 || dims[1] < 1) return MLT_ERR_INVALID_ARG;
+    if (dims[2] != 64 && dims[2] != 128) return MLT_ERR_UNSUPPORTED;
+    MhaArgs a{1, 1, dims[0], dims[1], dims[2], nullptr, nullptr, nullptr, nullptr, 1.f,
+              dims[3] ? 1 : 0, dtype};
+    MhaPlan p = plan_mha(a);
+    if (!p.supported) return MLT_ERR_UNSUPPORTED;
+    out[0] = p.bm; out[1] = (int32_t)dims[2]; out[2] = p.waves; out[3] = 1;
+    out[4] = p.bm / p.waves; out[5] = (int32_t)dims[2]; out[6] = 32; out[7] = 32; out[8] = 16;
+    out[9] = p.bn;
+    return MLT_OK;
+  }
+  return MLT_ERR_INVALID_ARG;
+}
+
+const char* mlt_status_string(int status) {
+  switch (status) {
+    case MLT_OK: return "ok";
+    case MLT_ERR_INVALID_ARG: return "invalid argument";
+    case MLT_ERR_UNSUPPORTED: return "unsupported configuration";
+    case MLT_ERR_LAUNCH: return "kernel launch failed";
+    case MLT_ERR_DEVICE: return "no usable gfx950 device";
+  }
+  return "unknown status";
+}
+
+const char* mlt_version(void) { return "0.1.0"; }
+
+}  // extern "C"

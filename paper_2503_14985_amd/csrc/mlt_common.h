@@ -1,0 +1,94 @@
+// Shared device-side vocabulary for the gfx950 kernels: 16-bit vector types, MFMA wrappers,
+// LDS helpers. Wave64 only; every layout fact below was checked on hardware with one-hot probes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mlt.h"
+
+namespace mlt {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define MLT_LDS __attribute__((address_space(3)))
+
+struct bf16_tag {};
+struct f16_tag {};
+
+// Element traits: the 8-wide MFMA operand type and the fp32 -> 16-bit conversion (RNE).
+template <typename Tag> struct Elem;
+template <> struct Elem<bf16_tag> {
+  typedef bf16x8 vec8;
+  static __device__ __forceinline__ uint16_t from_f32(float x) {
+    __bf16 h = (__bf16)x;  // v_cvt_pk_bf16_f32: round-to-nearest-even
+    return __builtin_bit_cast(uint16_t, h);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    f32x2 v = {lo, hi};
+    bf16x2 h = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+  }
+};
+template <> struct Elem<f16_tag> {
+  typedef f16x8 vec8;
+  static __device__ __forceinline__ uint16_t from_f32(float x) {
+    _Float16 h = (_Float16)x;  // v_cvt_f16_f32: round-to-nearest-even
+    return __builtin_bit_cast(uint16_t, h);
+  }
+  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    f32x2 v = {lo, hi};
+    f16x2 h = __builtin_convertvector(v, f16x2);
+    return __builtin_bit_cast(uint32_t, h);
+  }
+};
+
+// D(32x32) += A(32x16) * B(16x32). Lane l supplies A[l%32][8*(l/32) .. +7] and
+// B[8*(l/32) .. +7][l%32]; it owns D[8*(r/4) + 4*(l/32) + r%4][l%32] in register r (0..15).
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma32(f16x8 a, f16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+// D(16x16) += A(16x32) * B(32x16). Lane l supplies A[l%16][8*(l/16) .. +7] and
+// B[8*(l/16) .. +7][l%16]; it owns D[4*(l/16) + r][l%16] in register r (0..3).
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma16(f16x8 a, f16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// 16-byte LDS read of 8 consecutive 16-bit elements at a byte offset.
+template <typename V8>
+__device__ __forceinline__ V8 lds_read8(const char* smem, int byte_off) {
+  return *reinterpret_cast<const V8*>(smem + byte_off);
+}
+
+// Transposing LDS read (ds_read_b64_tr_b16). Within each group of 16 lanes, lane s = 4*j + c
+// supplies the address of row j, columns 4c..4c+3 of a 4x16 block of 16-bit elements; lane i of
+// the group receives column i of that block: (X[0][i], X[1][i], X[2][i], X[3][i]).
+__device__ __forceinline__ s16x4 lds_read_tr4(const char* smem, int byte_off) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (MLT_LDS s16x4*)((MLT_LDS char*)smem + byte_off));
+}
+
+template <typename V8>
+__device__ __forceinline__ V8 join_tr(s16x4 lo, s16x4 hi) {
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(V8, v);
+}
+
+}  // namespace mlt

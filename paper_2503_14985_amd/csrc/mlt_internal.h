@@ -1,0 +1,46 @@
+// Host-side plumbing shared by the entry points and the kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mlt {
+
+enum GemmVariant { GEMM_AUTO = -1, GEMM_ZERO = 0, GEMM_GENERAL = 1, GEMM_256 = 2, GEMM_128 = 3 };
+
+struct GemmArgs {
+  int64_t M, N, K;
+  const uint16_t* A; int64_t lda;
+  const uint16_t* B; int64_t ldb; int transB;
+  uint16_t* C; int64_t ldc;
+  int dtype;
+  int forced;  // GemmVariant or GEMM_AUTO
+};
+
+struct GemmPlan {
+  int variant = GEMM_GENERAL;
+  const char* name = "";
+  int bm = 0, bn = 0, bk = 0, wm = 0, wn = 0;
+};
+
+GemmPlan plan_gemm(const GemmArgs& g);
+int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s);
+
+struct MhaArgs {
+  int64_t B, H, Sq, Sk, D;
+  const uint16_t *Q, *K, *V;
+  uint16_t* O;
+  float scale;
+  int causal, dtype;
+};
+
+struct MhaPlan {
+  const char* name = "";
+  int bm = 0, bn = 0, waves = 0;
+  bool supported = false;
+};
+
+MhaPlan plan_mha(const MhaArgs& a);
+int run_mha(const MhaArgs& a, const MhaPlan& p, hipStream_t s);
+
+}  // namespace mlt

@@ -1,0 +1,138 @@
+"""Helpers for the GPU parity tests: run the HIP path through the binding, run the oracle on the
+same 16-bit patterns, compare with the stated tolerances."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2503_14985_amd import inputs
+
+GEMM_TOL = {inputs.BF16: 8e-3, inputs.FP16: 1e-3}       # |C - C_ref| <= tol * (|A||B|) + 1e-6
+MHA_TOL = {inputs.BF16: 1e-2, inputs.FP16: 2e-3}        # max |O - O_ref|
+
+
+def widen(bits, dtype):
+    """16-bit patterns -> float64 through the library dtype (exact)."""
+    return inputs.bits_to_torch(bits, dtype).double().numpy()
+
+
+def gemm_seam_samples(M, N, rng, tile=256, sub=32, nrand=65536, nlines=16):
+    """Positions for the sampled check: whole rows and columns on both sides of tile and
+    wavefront seams (and the first/last), plus uniformly random positions."""
+    def lines(n):
+        cand = {0, n - 1}
+        for s in (sub, 2 * sub, tile // 2, tile):
+            for b in (s - 1, s, n - s - 1, n - s):
+                if 0 <= b < n:
+                    cand.add(b)
+        cand = sorted(cand)
+        if len(cand) > nlines:
+            keep = {0, n - 1}
+            rest = [c for c in cand if c not in keep]
+            pick = rng.choice(len(rest), nlines - 2, replace=False)
+            cand = sorted(keep | {rest[i] for i in pick})
+        return np.array(cand, dtype=np.int64)
+    rws, cls = lines(M), lines(N)
+    r = [np.repeat(rws, N), np.tile(np.arange(M), len(cls)), rng.integers(0, M, nrand)]
+    c = [np.tile(np.arange(N), len(rws)), np.repeat(cls, M), rng.integers(0, N, nrand)]
+    return np.concatenate(r), np.concatenate(c)
+
+
+def check_gemm(A, B, C_gpu, dtype, transB, full_limit=1 << 28, seed=0):
+    """A, B: uint16 patterns (B is [N,K] when transB). C_gpu: torch tensor [M,N] from the HIP path.
+    Full oracle when M*N*K is small, seam + random samples otherwise. Returns stats."""
+    M, K = A.shape
+    N = B.shape[0] if transB else B.shape[1]
+    Cg = C_gpu.detach().cpu().double().numpy()
+    assert Cg.shape == (M, N)
+    tol = GEMM_TOL[dtype]
+    if M * N * max(K, 1) <= full_limit:
+        Cref, T = oracle.gemm(A, B, dtype, transB=transB)
+        err = np.abs(Cg - Cref)
+        bound = tol * T + 1e-6
+    else:
+        rng = np.random.default_rng(seed + 12345)
+        r, c = gemm_seam_samples(M, N, rng)
+        # k-contiguous copy of B for the oracle's inner loop (same matrix, other storage order)
+        Bt = B if transB else np.ascontiguousarray(B.T)
+        Cref, T = oracle.gemm_sampled(A, Bt, r, c, dtype, transB=True)
+        err = np.abs(Cg[r, c] - Cref)
+        bound = tol * T + 1e-6
+    worst = float(np.max(err / bound)) if err.size else 0.0
+    assert np.all(np.isfinite(Cg)), "non-finite output"
+    assert np.all(err <= bound), "GEMM parity: worst err/bound = %.3f, max err %.3g" % (worst, err.max())
+    return {"max_err": float(err.max()) if err.size else 0.0, "worst_ratio": worst, "n": int(err.size)}
+
+
+def _device_matrix(bits, dtype, dev, ld=None):
+    """Upload a matrix; with ld > columns it becomes a row-strided view into a NaN-filled buffer."""
+    t = inputs.bits_to_torch(np.ascontiguousarray(bits), dtype, dev)
+    if ld is None or ld == bits.shape[1]:
+        return t
+    buf = torch.full((bits.shape[0], ld), float("nan"), dtype=t.dtype, device=dev)
+    buf[:, : bits.shape[1]] = t
+    return buf[:, : bits.shape[1]]
+
+
+def run_gemm(A, B, dtype, transB=False, device="cuda:0", lda=None, ldb=None, ldc_pad=0):
+    from paper_2503_14985_amd import binding
+    dev = torch.device(device)
+    tA = _device_matrix(A, dtype, dev, lda)
+    tB = _device_matrix(B, dtype, dev, ldb)
+    C = None
+    M = A.shape[0]
+    N = B.shape[0] if transB else B.shape[1]
+    if ldc_pad:
+        buf = torch.full((M, N + ldc_pad), float("nan"), dtype=tA.dtype, device=dev)
+        C = buf[:, :N]
+    out = binding.mlt_gemm(tA, tB, C=C, transB=transB)
+    torch.cuda.synchronize()
+    if ldc_pad:
+        assert torch.isnan(buf[:, N:]).all(), "kernel wrote into the padding of C"
+    return out
+
+
+def mha_sample_rows(B, H, Sq, rng, n_bh=8, n_rows=512, tile=128):
+    bh = {(0, 0), (B - 1, H - 1)}
+    while len(bh) < min(n_bh, B * H):
+        bh.add((int(rng.integers(0, B)), int(rng.integers(0, H))))
+    rows = {0, 1, 2, 3, Sq - 1}
+    for t in range(tile, Sq, tile):
+        rows.update((t - 1, t))
+        if len(rows) > n_rows // 2:
+            break
+    rows = sorted(r for r in rows if 0 <= r < Sq)
+    bs, hs, qs = [], [], []
+    for (b, h) in sorted(bh):
+        extra = rng.integers(0, Sq, max(0, n_rows - len(rows)))
+        for r in list(rows) + list(extra):
+            bs.append(b); hs.append(h); qs.append(int(r))
+    return np.array(bs), np.array(hs), np.array(qs)
+
+
+def check_mha(Q, K, V, O_gpu, scale, causal, dtype, full_limit=1 << 31, seed=0):
+    B, H, Sq, D = Q.shape
+    Sk = K.shape[2]
+    Og = O_gpu.detach().cpu().double().numpy()
+    assert np.all(np.isfinite(Og)), "non-finite output"
+    if B * H * Sq * Sk * D <= full_limit:
+        Oref = oracle.mha_fwd(Q, K, V, scale, causal, dtype)
+        got = Og
+    else:
+        rng = np.random.default_rng(seed + 777)
+        bs, hs, qs = mha_sample_rows(B, H, Sq, rng)
+        Oref = oracle.mha_fwd_rows(Q, K, V, bs, hs, qs, scale, causal, dtype)
+        got = Og[bs, hs, qs]
+    err = np.abs(got - Oref)
+    rel_rms = float(np.sqrt(np.mean(err ** 2)) / max(np.sqrt(np.mean(Oref ** 2)), 1e-30))
+    mx = float(err.max())
+    assert mx <= MHA_TOL[dtype], "attention parity: max err %.3g (rel rms %.3g)" % (mx, rel_rms)
+    return {"max_err": mx, "rel_rms": rel_rms, "n": int(err.size)}
+
+
+def run_mha(Q, K, V, scale, causal, dtype, device="cuda:0"):
+    from paper_2503_14985_amd import binding
+    dev = torch.device(device)
+    tq, tk, tv = (inputs.bits_to_torch(x, dtype, dev) for x in (Q, K, V))
+    O = binding.mlt_mha_fwd(tq, tk, tv, scale=scale, causal=causal)
+    torch.cuda.synchronize()
+    return O

@@ -1,0 +1,118 @@
+"""GPU parity of mlt_gemm against the fp64 oracle (through the C ABI via the ctypes binding)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_14985_amd import inputs
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+BF16, FP16 = inputs.BF16, inputs.FP16
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print("\n[case] %s" % request.node.name, flush=True)
+    os.environ.pop("MLT_GEMM_VARIANT", None)
+    yield
+    os.environ.pop("MLT_GEMM_VARIANT", None)
+
+
+def _go(M, N, K, dtype, transB, dist="normal", std=1.0, seed=0, variant=None, **pads):
+    from paper_2503_14985_amd import binding
+    A, B = inputs.gemm_inputs(M, N, K, dtype, seed, dist=dist, std=std, transB=transB)
+    if variant:
+        os.environ["MLT_GEMM_VARIANT"] = variant
+    C = pu.run_gemm(A, B, dtype, transB=transB, lda=pads.get("lda"), ldb=pads.get("ldb"),
+                    ldc_pad=pads.get("ldc_pad", 0))
+    st = pu.check_gemm(A, B, C, dtype, transB, seed=seed)
+    print("   kernel=%s %s" % (binding.mlt_last_kernel(), st), flush=True)
+    return binding.mlt_last_kernel(), st
+
+
+def test_config1_bf16_512_uniform():
+    name, _ = _go(512, 512, 512, BF16, False, dist="uniform")
+    assert name.startswith("gemm_nn")
+
+
+@pytest.mark.parametrize("variant", ["256", "128", "general"])
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+def test_small_multi_tile_ragged(variant, transB, dtype):
+    # several tiles of every variant in both directions plus ragged tails in M, N and K
+    _go(520, 776, 328, dtype, transB, variant=variant, seed=1)
+
+
+@pytest.mark.parametrize("variant", ["256", "128"])
+@pytest.mark.parametrize("transB", [False, True])
+def test_exact_tiles(variant, transB):
+    _go(512, 768, 256, BF16, transB, variant=variant, seed=2)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (37, 53, 29), (65, 63, 33), (16, 8, 8), (8, 16, 24),
+                                   (255, 257, 64), (3, 1000, 2048)])
+@pytest.mark.parametrize("transB", [False, True])
+def test_odd_shapes(shape, transB):
+    M, N, K = shape
+    _go(M, N, K, BF16, transB, seed=3)
+    _go(M, N, K, FP16, transB, seed=3)
+
+
+@pytest.mark.parametrize("transB", [False, True])
+def test_padded_leading_dimensions(transB):
+    K, N = 200, 264
+    _go(300, N, K, BF16, transB, seed=4, lda=K + 8, ldb=(K if transB else N) + 16, ldc_pad=5)
+    # unaligned leading dimensions must fall back to the general kernel and still be right
+    name, _ = _go(70, N, K, BF16, transB, seed=4, lda=K + 3, ldb=(K if transB else N) + 1, ldc_pad=1)
+    assert "general" in name
+
+
+def test_k_zero_and_empty():
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    A = torch.empty((5, 0), dtype=torch.bfloat16, device=dev)
+    B = torch.empty((0, 7), dtype=torch.bfloat16, device=dev)
+    C = torch.full((5, 7), float("nan"), dtype=torch.bfloat16, device=dev)
+    binding.mlt_gemm(A, B, C=C)
+    torch.cuda.synchronize()
+    assert torch.all(C == 0)
+    C0 = binding.mlt_gemm(torch.empty((0, 8), dtype=torch.float16, device=dev),
+                          torch.empty((8, 4), dtype=torch.float16, device=dev))
+    assert C0.shape == (0, 4)
+
+
+def test_integer_exact_and_identity():
+    """Small integers: fp32 accumulation is exact, so the GPU must equal the oracle exactly."""
+    from paper_2503_14985_amd import binding
+    rng = np.random.default_rng(5)
+    M, N, K = 300, 264, 136
+    a = rng.integers(-4, 5, (M, K)).astype(np.float32)
+    b = rng.integers(-4, 5, (K, N)).astype(np.float32)
+    A, B = inputs.to_bits(a, BF16), inputs.to_bits(b, BF16)
+    C = pu.run_gemm(A, B, BF16)
+    import oracle
+    Cref, _ = oracle.gemm(A, B, BF16)
+    # |C| <= 16*136 = 2176 needs 12 bits: not exact in bf16; compare after rounding the oracle
+    want = np.array([oracle.round_to_dtype(v, BF16) for v in Cref.ravel()]).reshape(M, N)
+    assert np.array_equal(C.double().cpu().numpy(), want)
+    eye = inputs.to_bits(np.eye(256, dtype=np.float32), BF16)
+    X = inputs.to_bits(rng.standard_normal((256, 256)).astype(np.float32), BF16)
+    Y = pu.run_gemm(X, eye, BF16)
+    assert np.array_equal(inputs.torch_to_bits(Y), X)
+    Y = pu.run_gemm(eye, X, BF16, transB=True)             # I * (X^T stored as X) = X^T
+    assert np.array_equal(inputs.torch_to_bits(Y), np.ascontiguousarray(X.T))
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+@pytest.mark.parametrize("n", [1024, 2048, 4096, 8192])
+def test_config2_square_sweep(dtype, n):
+    _go(n, n, n, dtype, False, seed=0)
+
+
+@pytest.mark.parametrize("shape", [(4096, 14336, 4096), (4096, 4096, 14336), (8192, 28672, 8192),
+                                   (16, 4096, 4096)])
+def test_config3_llm_shapes_transB(shape):
+    M, N, K = shape
+    _go(M, N, K, BF16, True, std=0.02, seed=0)
