@@ -69,11 +69,12 @@ struct GemmTile {
   static constexpr int TM = BM / WM / 32;               // MFMA tiles per wavefront
   static constexpr int TN = BN / WN / 32;
   static_assert(BM * KC % NT == 0 && BN * KC % NT == 0, "tile must split evenly over threads");
+  static_assert(NT % KC == 0 && NT % (BN / 8) == 0, "a thread's chunks must share their column");
   static_assert(BK % 16 == 0 && BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "MFMA tiling");
 };
 
 template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB>
-__global__ __launch_bounds__(WM* WN * 64, 1) void gemm_tile_kernel(
+__global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
     int nbn) {
@@ -88,71 +89,89 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_tile_kernel(
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   // ---- per-thread staging assignments (fixed for the whole K loop)
+  // Chunk c = tid + i*NT of a [rows][KC] tile is (row c / KC, k chunk c % KC). NT is a multiple of
+  // KC, so the k chunk is the same for every i and row_i = row_0 + i * (NT / KC): LDS offsets
+  // differ by compile-time constants and only the clamped global row pointers are per-i values.
+  constexpr int RSTEP = Cfg::NT / Cfg::KC;              // tile rows between a thread's chunks
+  const int st_row = tid / Cfg::KC, st_k = (tid % Cfg::KC) * 8;
   const uint16_t* a_src[Cfg::NA];
-  int a_dst[Cfg::NA], a_k[Cfg::NA];
 #pragma unroll
   for (int i = 0; i < Cfg::NA; ++i) {
-    const int c = tid + i * Cfg::NT;
-    const int row = c / Cfg::KC, kc = c % Cfg::KC;
-    int grow = m0 + row;
+    int grow = m0 + st_row + i * RSTEP;
     grow = grow < M ? grow : M - 1;
-    a_src[i] = A + (int64_t)grow * lda + kc * 8;
-    a_dst[i] = (row * Cfg::LDA_S + kc * 8) * 2;
-    a_k[i] = kc * 8;
+    a_src[i] = A + (int64_t)grow * lda + st_k;
   }
-  const uint16_t* b_src[Cfg::NB];
-  int b_dst[Cfg::NB], b_k[Cfg::NB];
+  const int a_dst = (st_row * Cfg::LDA_S + st_k) * 2;
+  constexpr int A_DST_STEP = RSTEP * Cfg::LDA_S * 2;
+
+  const uint16_t* b_src[TRANSB ? Cfg::NB : 1];
+  int b_dst, b_k;
+  constexpr int NC = BN / 8;                            // 16-byte chunks along n (row-major B)
+  constexpr int KSTEP = Cfg::NT / NC;                   // k rows between a thread's chunks
+  constexpr int B_DST_STEP = (TRANSB ? RSTEP : KSTEP) * Cfg::LDB_S * 2;
+  if (TRANSB) {
 #pragma unroll
-  for (int i = 0; i < Cfg::NB; ++i) {
-    const int c = tid + i * Cfg::NT;
-    if (TRANSB) {
-      const int row = c / Cfg::KC, kc = c % Cfg::KC;
-      int grow = n0 + row;
+    for (int i = 0; i < Cfg::NB; ++i) {
+      int grow = n0 + st_row + i * RSTEP;
       grow = grow < N ? grow : N - 1;
-      b_src[i] = B + (int64_t)grow * ldb + kc * 8;
-      b_dst[i] = Cfg::A_BYTES + (row * Cfg::LDB_S + kc * 8) * 2;
-      b_k[i] = kc * 8;
-    } else {
-      constexpr int NC = BN / 8;                        // chunks along n
-      const int krow = c / NC, nc = c % NC;
-      const int gcol = n0 + nc * 8;
-      // N % 8 == 0: a chunk is all in or all out; an outside chunk reads column 0 instead
-      b_src[i] = B + (int64_t)krow * ldb + (gcol < N ? gcol : 0);
-      b_dst[i] = Cfg::A_BYTES + (krow * Cfg::LDB_S + nc * 8) * 2;
-      b_k[i] = krow;
+      b_src[i] = B + (int64_t)grow * ldb + st_k;
     }
+    b_dst = Cfg::A_BYTES + (st_row * Cfg::LDB_S + st_k) * 2;
+    b_k = st_k;
+  } else {
+    const int krow = tid / NC, nc = tid % NC;
+    const int gcol = n0 + nc * 8;
+    // N % 8 == 0: a chunk is all in or all out; an outside chunk reads column 0 instead
+    b_src[0] = B + (int64_t)krow * ldb + (gcol < N ? gcol : 0);
+    b_dst = Cfg::A_BYTES + (krow * Cfg::LDB_S + nc * 8) * 2;
+    b_k = krow;
   }
 
   u32x4 ga[Cfg::NA], gb[Cfg::NB];
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-  // Loads never branch: a chunk outside the matrix re-reads a valid address (row clamp above,
-  // column 0 / k 0 here); only chunks past K, which would pollute real outputs, are zeroed.
-  auto load_global = [&](int k0, bool tail) {
+  // Loads never branch per element: a chunk outside the matrix re-reads a valid address (row
+  // clamp above, column 0 here). Only the last K step can run past K; it takes the second form,
+  // which re-reads k = 0 for chunks past K and zeroes them (they would pollute real outputs).
+  auto load_global_full = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < Cfg::NA; ++i) ga[i] = *reinterpret_cast<const u32x4_mem*>(a_src[i] + k0);
+#pragma unroll
+    for (int i = 0; i < Cfg::NB; ++i) {
+      if (TRANSB) gb[i] = *reinterpret_cast<const u32x4_mem*>(b_src[i] + k0);
+      else gb[i] = *reinterpret_cast<const u32x4_mem*>(b_src[0] + (int64_t)(k0 + i * KSTEP) * ldb);
+    }
+  };
+  auto load_global_tail = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < Cfg::NA; ++i) {
-      const bool ok = !tail || (k0 + a_k[i] < K);
-      const u32x4 v = *reinterpret_cast<const u32x4*>(a_src[i] + (ok ? k0 : -a_k[i]));
+      const bool ok = k0 + st_k < K;
+      const u32x4 v = *reinterpret_cast<const u32x4_mem*>(a_src[i] + (ok ? k0 : -st_k));
       ga[i] = ok ? v : zero4;
     }
 #pragma unroll
     for (int i = 0; i < Cfg::NB; ++i) {
-      const bool ok = !tail || (k0 + b_k[i] < K);
-      u32x4 v;
       if (TRANSB) {
-        v = *reinterpret_cast<const u32x4*>(b_src[i] + (ok ? k0 : -b_k[i]));
+        const bool ok = k0 + b_k < K;
+        const u32x4 v = *reinterpret_cast<const u32x4_mem*>(b_src[i] + (ok ? k0 : -b_k));
+        gb[i] = ok ? v : zero4;
       } else {
-        v = *reinterpret_cast<const u32x4*>(b_src[i] + (ok ? (int64_t)k0 * ldb : -(int64_t)b_k[i] * ldb));
+        const int kr = k0 + i * KSTEP;                  // + b_k = the k row of this chunk
+        const bool ok = kr + b_k < K;
+        const u32x4 v = *reinterpret_cast<const u32x4_mem*>(b_src[0] + (int64_t)(ok ? kr : -b_k) * ldb);
+        gb[i] = ok ? v : zero4;
       }
-      gb[i] = ok ? v : zero4;
     }
+  };
+  auto load_global = [&](int k0, bool tail) {
+    if (tail) load_global_tail(k0); else load_global_full(k0);
   };
   auto store_lds = [&](int stage) {
     char* base = smem + stage * Cfg::STAGE;
 #pragma unroll
-    for (int i = 0; i < Cfg::NA; ++i) *reinterpret_cast<u32x4*>(base + a_dst[i]) = ga[i];
+    for (int i = 0; i < Cfg::NA; ++i) *reinterpret_cast<u32x4_mem*>(base + a_dst + i * A_DST_STEP) = ga[i];
 #pragma unroll
-    for (int i = 0; i < Cfg::NB; ++i) *reinterpret_cast<u32x4*>(base + b_dst[i]) = gb[i];
+    for (int i = 0; i < Cfg::NB; ++i) *reinterpret_cast<u32x4_mem*>(base + b_dst + i * B_DST_STEP) = gb[i];
   };
 
   // ---- fragment addresses inside a stage
@@ -179,41 +198,86 @@ __global__ __launch_bounds__(WM* WN * 64, 1) void gemm_tile_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // Fragments of k slice kk of a stage: TM A operands and TN B operands.
+  auto load_frags = [&](const char* st, int kk, V8 (&af)[Cfg::TM], V8 (&bf)[Cfg::TN]) {
+#pragma unroll
+    for (int i = 0; i < Cfg::TM; ++i)
+      af[i] = lds_read8<V8>(st, a_frag + (i * 32 * Cfg::LDA_S + kk * 16) * 2);
+#pragma unroll
+    for (int j = 0; j < Cfg::TN; ++j) {
+      if (TRANSB) {
+        bf[j] = lds_read8<V8>(st, b_frag + (j * 32 * Cfg::LDB_S + kk * 16) * 2);
+      } else {
+        const int off = b_frag + (kk * 16 * Cfg::LDB_S + j * 32) * 2;
+        s16x4 lo = lds_read_tr4(st, off);
+        s16x4 hi = lds_read_tr4(st, off + 4 * Cfg::LDB_S * 2);
+        bf[j] = join_tr<V8>(lo, hi);
+      }
+    }
+  };
+
   const int KT = (K + BK - 1) / BK;
   const bool ragged_k = (K % BK) != 0;                  // only the last step can be partial
+  constexpr int NKK = BK / 16;
+  static_assert(NKK == 4, "the schedule below is written for four k slices per stage");
+
+  // Software pipeline. Stage s holds tile kt (s = kt & 1). During step kt:
+  //   slice 0: read fragments of slice 1 | MFMAs of slice 0
+  //   slice 1: read fragments of slice 2 | MFMAs of slice 1 | write tile kt+1 (already in
+  //            registers since the previous step) to the other stage | issue the global loads
+  //            of tile kt+2 into the registers just freed
+  //   slice 2: read fragments of slice 3 | MFMAs of slice 2 | barrier
+  //   slice 3: read fragments of slice 0 of tile kt+1 | MFMAs of slice 3
+  // The barrier sits where every wavefront has issued its last read of stage s and its writes
+  // of tile kt+1, so after it stage s may be overwritten (in step kt+1) and tile kt+1 may be
+  // read; its latency and that of the first fragment reads hide behind the MFMAs of slice 3.
   load_global(0, ragged_k && KT == 1);
   store_lds(0);
+  if (KT > 1) load_global(BK, ragged_k && KT == 2);
   __syncthreads();
+
+  V8 af[2][Cfg::TM], bf[2][Cfg::TN];
+  load_frags(smem, 0, af[0], bf[0]);
+
+  auto mfma_slice = [&](int which) {
+#pragma unroll
+    for (int i = 0; i < Cfg::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < Cfg::TN; ++j)
+        acc[i][j] = mfma32(af[which][i], bf[which][j], acc[i][j]);
+  };
 
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
-    const bool more = kt + 1 < KT;
-    if (more) load_global((kt + 1) * BK, ragged_k && kt + 2 == KT);
     const char* st = smem + cur * Cfg::STAGE;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      V8 af[Cfg::TM], bf[Cfg::TN];
-#pragma unroll
-      for (int i = 0; i < Cfg::TM; ++i)
-        af[i] = lds_read8<V8>(st, a_frag + (i * 32 * Cfg::LDA_S + kk * 16) * 2);
-#pragma unroll
-      for (int j = 0; j < Cfg::TN; ++j) {
-        if (TRANSB) {
-          bf[j] = lds_read8<V8>(st, b_frag + (j * 32 * Cfg::LDB_S + kk * 16) * 2);
-        } else {
-          const int off = b_frag + (kk * 16 * Cfg::LDB_S + j * 32) * 2;
-          s16x4 lo = lds_read_tr4(st, off);
-          s16x4 hi = lds_read_tr4(st, off + 4 * Cfg::LDB_S * 2);
-          bf[j] = join_tr<V8>(lo, hi);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < Cfg::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < Cfg::TN; ++j) acc[i][j] = mfma32(af[i], bf[j], acc[i][j]);
+    const char* nx = smem + (cur ^ 1) * Cfg::STAGE;
+    const bool have_next = kt + 1 < KT;
+
+    load_frags(st, 1, af[1], bf[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_slice(0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    load_frags(st, 2, af[0], bf[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_slice(1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (have_next) {
+      store_lds(cur ^ 1);
+      if (kt + 2 < KT) load_global((kt + 2) * BK, ragged_k && kt + 3 == KT);
     }
-    if (more) store_lds(cur ^ 1);
+    __builtin_amdgcn_sched_barrier(0);
+
+    load_frags(st, 3, af[1], bf[1]);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_slice(0);                                      // slice 2 lives in fragment set 0
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+
+    if (have_next) load_frags(nx, 0, af[0], bf[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_slice(1);                                      // slice 3 lives in fragment set 1
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   // ---- epilogue: fp32 -> 16-bit (RNE), guarded element stores
@@ -274,8 +338,8 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       const int off = kk * 16 + 8 * (lane >> 5);
-      V8 a = *reinterpret_cast<const V8*>(&As[(wm * 32 + (lane & 31)) * LDS_S + off]);
-      V8 b = *reinterpret_cast<const V8*>(&Bs[(wn * 32 + (lane & 31)) * LDS_S + off]);
+      V8 a = lds_read8<V8>(reinterpret_cast<const char*>(As), ((wm * 32 + (lane & 31)) * LDS_S + off) * 2);
+      V8 b = lds_read8<V8>(reinterpret_cast<const char*>(Bs), ((wn * 32 + (lane & 31)) * LDS_S + off) * 2);
       acc = mfma32(a, b, acc);
     }
     __syncthreads();
@@ -344,12 +408,27 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   }
   // Big tile when it still fills the chip, otherwise the small one.
   const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-  int v = tiles256 >= 192 ? GEMM_256 : GEMM_128;
-  if (g.forced == GEMM_256 || g.forced == GEMM_128) v = g.forced;
+  int v = tiles256 >= 192 ? GEMM_256_W8 : GEMM_128;
+  if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS) v = g.forced;
   p.variant = v;
-  if (v == GEMM_256) { p.bm = 256; p.bn = 256; p.bk = 64; p.wm = 2; p.wn = 2; p.name = g.transB ? "gemm_nt_256x256x64" : "gemm_nn_256x256x64"; }
-  else { p.bm = 128; p.bn = 128; p.bk = 64; p.wm = 2; p.wn = 2; p.name = g.transB ? "gemm_nt_128x128x64" : "gemm_nn_128x128x64"; }
+  p.bk = 64;
+  switch (v) {
+    case GEMM_256: p.bm = p.bn = 256; p.wm = 2; p.wn = 2;
+      p.name = g.transB ? "gemm_nt_256x256x64_w2x2" : "gemm_nn_256x256x64_w2x2"; break;
+    case GEMM_256_W8: p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
+      p.name = g.transB ? "gemm_nt_256x256x64_w2x4" : "gemm_nn_256x256x64_w2x4"; break;
+    case GEMM_256_W8T: p.bm = p.bn = 256; p.wm = 4; p.wn = 2;
+      p.name = g.transB ? "gemm_nt_256x256x64_w4x2" : "gemm_nn_256x256x64_w4x2"; break;
+    default: p.bm = p.bn = 128; p.wm = 2; p.wn = 2;
+      p.name = g.transB ? "gemm_nt_128x128x64_w2x2" : "gemm_nn_128x128x64_w2x2"; break;
+  }
   return p;
+}
+
+template <typename Tag, int BM, int BN, int BK, int WM, int WN>
+static int launch_tile_tb(const GemmArgs& g, hipStream_t s) {
+  return g.transB ? launch_tile<Tag, BM, BN, BK, WM, WN, true>(g, s)
+                  : launch_tile<Tag, BM, BN, BK, WM, WN, false>(g, s);
 }
 
 template <typename Tag>
@@ -362,12 +441,10 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
       return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
     }
     case GEMM_GENERAL: return launch_general<Tag>(g, s);
-    case GEMM_256:
-      return g.transB ? launch_tile<Tag, 256, 256, 64, 2, 2, true>(g, s)
-                      : launch_tile<Tag, 256, 256, 64, 2, 2, false>(g, s);
-    case GEMM_128:
-      return g.transB ? launch_tile<Tag, 128, 128, 64, 2, 2, true>(g, s)
-                      : launch_tile<Tag, 128, 128, 64, 2, 2, false>(g, s);
+    case GEMM_256: return launch_tile_tb<Tag, 256, 256, 64, 2, 2>(g, s);
+    case GEMM_256_W8: return launch_tile_tb<Tag, 256, 256, 64, 2, 4>(g, s);
+    case GEMM_256_W8T: return launch_tile_tb<Tag, 256, 256, 64, 4, 2>(g, s);
+    case GEMM_128: return launch_tile_tb<Tag, 128, 128, 64, 2, 2>(g, s);
   }
   return MLT_ERR_UNSUPPORTED;
 }

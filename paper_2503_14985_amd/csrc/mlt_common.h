@@ -17,6 +17,11 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+// Every 16-byte memory access (global or LDS) goes through this one type, marked may_alias: the
+// same LDS bytes are written as raw dwords and read back as 16-bit vectors, and type-based alias
+// analysis would otherwise be free to treat those reads as unrelated to the writes.
+typedef u32x4 __attribute__((may_alias)) u32x4_mem;
+typedef u32x2 __attribute__((may_alias)) u32x2_mem;
 
 #define MLT_LDS __attribute__((address_space(3)))
 
@@ -74,7 +79,8 @@ __device__ __forceinline__ f32x4 mfma16(f16x8 a, f16x8 b, f32x4 c) {
 // 16-byte LDS read of 8 consecutive 16-bit elements at a byte offset.
 template <typename V8>
 __device__ __forceinline__ V8 lds_read8(const char* smem, int byte_off) {
-  return *reinterpret_cast<const V8*>(smem + byte_off);
+  const u32x4 raw = *reinterpret_cast<const u32x4_mem*>(smem + byte_off);
+  return __builtin_bit_cast(V8, raw);
 }
 
 // Transposing LDS read (ds_read_b64_tr_b16). Within each group of 16 lanes, lane s = 4*j + c

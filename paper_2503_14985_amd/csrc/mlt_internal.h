@@ -6,7 +6,14 @@
 
 namespace mlt {
 
-enum GemmVariant { GEMM_AUTO = -1, GEMM_ZERO = 0, GEMM_GENERAL = 1, GEMM_256 = 2, GEMM_128 = 3 };
+enum GemmVariant {
+  GEMM_AUTO = -1, GEMM_ZERO = 0, GEMM_GENERAL = 1,
+  GEMM_256 = 2,       // 256x256x64, 4 wavefronts (2x2) of 128x128
+  GEMM_128 = 3,       // 128x128x64, 4 wavefronts (2x2) of 64x64
+  GEMM_256_W8 = 4,    // 256x256x64, 8 wavefronts (2x4) of 128x64
+  GEMM_256_W8T = 5,   // 256x256x64, 8 wavefronts (4x2) of 64x128
+  GEMM_NUM_VARIANTS
+};
 
 struct GemmArgs {
   int64_t M, N, K;
