@@ -109,7 +109,8 @@ def mha_sample_rows(B, H, Sq, rng, n_bh=8, n_rows=512, tile=128):
     return np.array(bs), np.array(hs), np.array(qs)
 
 
-def check_mha(Q, K, V, O_gpu, scale, causal, dtype, full_limit=1 << 31, seed=0):
+def check_mha(Q, K, V, O_gpu, scale, causal, dtype, full_limit=1 << 31, seed=0, n_rows=512,
+              rounding_aware=False):
     B, H, Sq, D = Q.shape
     Sk = K.shape[2]
     Og = O_gpu.detach().cpu().double().numpy()
@@ -119,13 +120,21 @@ def check_mha(Q, K, V, O_gpu, scale, causal, dtype, full_limit=1 << 31, seed=0):
         got = Og
     else:
         rng = np.random.default_rng(seed + 777)
-        bs, hs, qs = mha_sample_rows(B, H, Sq, rng)
+        bs, hs, qs = mha_sample_rows(B, H, Sq, rng, n_rows=n_rows)
         Oref = oracle.mha_fwd_rows(Q, K, V, bs, hs, qs, scale, causal, dtype)
         got = Og[bs, hs, qs]
     err = np.abs(got - Oref)
     rel_rms = float(np.sqrt(np.mean(err ** 2)) / max(np.sqrt(np.mean(Oref ** 2)), 1e-30))
     mx = float(err.max())
-    assert mx <= MHA_TOL[dtype], "attention parity: max err %.3g (rel rms %.3g)" % (mx, rel_rms)
+    if rounding_aware:
+        # Inputs built so that |O| ~ |V| (up to ~4): one rounding of the output alone can exceed
+        # the absolute bound (bf16 half-ulp at 4 is 1.6e-2). Allow that rounding, and hold the
+        # arithmetic to a bound several times tighter than the graded one.
+        ulp_rel = 2.0 ** -8 if dtype == inputs.BF16 else 2.0 ** -11
+        bound = ulp_rel * np.abs(Oref) + 0.4 * MHA_TOL[dtype]
+        assert np.all(err <= bound), "attention parity (rounding-aware): worst err/bound %.3f" % float(np.max(err / bound))
+    else:
+        assert mx <= MHA_TOL[dtype], "attention parity: max err %.3g (rel rms %.3g)" % (mx, rel_rms)
     return {"max_err": mx, "rel_rms": rel_rms, "n": int(err.size)}
 
 

@@ -1,0 +1,112 @@
+"""GPU parity of mlt_mha_fwd against the fp64 oracle (through the C ABI via the ctypes binding)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_14985_amd import inputs
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+BF16, FP16 = inputs.BF16, inputs.FP16
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print("\n[case] %s" % request.node.name, flush=True)
+    yield
+
+
+def _go(B, H, Sq, Sk, D, dtype, causal, seed=0, scale=None, q_gain=1.0, **kw):
+    from paper_2503_14985_amd import binding
+    Q, K, V = inputs.mha_inputs(B, H, Sq, Sk, D, dtype, seed, q_gain=q_gain)
+    scale = 1.0 / math.sqrt(D) if scale is None else scale
+    O = pu.run_mha(Q, K, V, scale, causal, dtype)
+    st = pu.check_mha(Q, K, V, O, scale, causal, dtype, seed=seed, **kw)
+    print("   kernel=%s %s" % (binding.mlt_last_kernel(), st), flush=True)
+    return st
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("D", [64, 128])
+def test_small_multi_tile(dtype, causal, D):
+    # 2 query tiles of 256 and 5 key tiles of 64
+    st = _go(1, 2, 512, 320, D, dtype, causal, seed=1)
+    # sharper than the graded bound: output rounding plus P rounding only
+    assert st["rel_rms"] < (1.5e-2 if dtype == BF16 else 2e-3)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (1, 1, 7, 1), (1, 3, 33, 17), (2, 2, 300, 200),
+                                   (1, 2, 200, 300), (1, 1, 257, 65), (1, 1, 64, 1000)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_ragged_shapes(shape, causal):
+    B, H, Sq, Sk = shape
+    _go(B, H, Sq, Sk, 128, BF16, causal, seed=2)
+    _go(B, H, Sq, Sk, 64, FP16, causal, seed=2)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_peaky_scores_sharp_check(causal):
+    """Q scaled x6: softmax concentrates, |O| ~ |V|, so the absolute bound bites."""
+    st = _go(1, 2, 384, 384, 128, BF16, causal, seed=3, q_gain=6.0, rounding_aware=True)
+    assert st["rel_rms"] < 1.5e-2
+    st = _go(1, 2, 384, 384, 64, FP16, causal, seed=3, q_gain=6.0, rounding_aware=True)
+    assert st["rel_rms"] < 2e-3
+
+
+@pytest.mark.parametrize("scale", [0.0, -0.2, 1.0, 1e-3])
+def test_scale_edge_values(scale):
+    # scale = 1 makes the softmax peaky (|O| ~ |V|): see the rounding-aware bound
+    _go(1, 2, 130, 190, 128, BF16, False, seed=4, scale=scale, rounding_aware=True)
+    _go(1, 2, 130, 190, 64, BF16, True, seed=4, scale=scale, rounding_aware=True)
+
+
+def test_structural_pins_on_gpu():
+    """Q = 0 gives the mean of the visible V rows; causal row 0 is V[0]; constant V comes back."""
+    B, H, S, D = 1, 2, 320, 128
+    rng = np.random.default_rng(5)
+    Q, K, V = inputs.mha_inputs(B, H, S, S, D, BF16, 5)
+    Vd = pu.widen(V, BF16)
+    Z = np.zeros_like(Q)
+    O = pu.run_mha(Z, K, V, 0.3, False, BF16).double().cpu().numpy()
+    assert np.max(np.abs(O - Vd.mean(axis=2, keepdims=True))) < 2e-3
+    Oc = pu.run_mha(Z, K, V, 0.3, True, BF16).double().cpu().numpy()
+    prefix = np.cumsum(Vd, axis=2) / np.arange(1, S + 1)[None, None, :, None]
+    assert np.max(np.abs(Oc - prefix)) < 1e-2
+    Oc = pu.run_mha(Q, K, V, 0.3, True, BF16)
+    assert np.array_equal(inputs.torch_to_bits(Oc)[:, :, 0, :], V[:, :, 0, :])   # row 0 = V[0] exactly
+    v = inputs.to_bits(rng.standard_normal(D).astype(np.float32), BF16)
+    Vc = np.broadcast_to(v, (B, H, S, D)).copy()
+    Oc = pu.run_mha(Q, K, Vc, 0.3, False, BF16).double().cpu().numpy()
+    assert np.max(np.abs(Oc - pu.widen(v, BF16)[None, None, None, :])) < 1.6e-2  # one bf16 ulp at |v|<4
+
+
+def test_error_codes_on_gpu():
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    q = torch.zeros((1, 1, 4, 96), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(binding.MltError) as e:
+        binding.mlt_mha_fwd(q, q, q, 1.0)
+    assert e.value.status == binding.MLT_ERR_UNSUPPORTED
+    q = torch.zeros((1, 1, 4, 64), dtype=torch.bfloat16, device=dev)
+    k = torch.zeros((1, 1, 0, 64), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(binding.MltError) as e:
+        binding.mlt_mha_fwd(q, k, k, 1.0)
+    assert e.value.status == binding.MLT_ERR_INVALID_ARG
+    o = binding.mlt_mha_fwd(q[:, :, :0], q, q, 1.0)       # Sq = 0: no-op
+    assert o.shape == (1, 1, 0, 64)
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+def test_config4_noncausal_full_size(dtype):
+    st = _go(4, 32, 4096, 4096, 128, dtype, False, seed=0)
+    assert st["rel_rms"] < (1.5e-2 if dtype == BF16 else 2e-3)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("S", [1024, 4096, 16384])
+def test_config5_causal(S, D):
+    _go(1, 32, S, S, D, BF16, True, seed=0, n_rows=512 if S <= 4096 else 160)
