@@ -69,7 +69,7 @@ int mlt_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const 
  *
  * D must be 64 or 128 (else MLT_ERR_UNSUPPORTED). B, H or Sq equal to 0 is a no-op. Sk must be
  * >= 1 (a softmax over no keys is undefined: MLT_ERR_INVALID_ARG). All four base pointers must
- * be 16-byte aligned (MLT_ERR_INVALID_ARG otherwise).
+ * be 16-byte aligned and scale must be finite (MLT_ERR_INVALID_ARG otherwise).
  */
 int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const void* Q,
                 const void* K, const void* V, void* O, float scale, int causal, int dtype,

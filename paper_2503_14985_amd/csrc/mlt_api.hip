@@ -59,7 +59,7 @@ int check_mha(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const voi
               const void* K, const void* V, const void* O, float scale, int dtype) {
   if (dtype != MLT_BF16 && dtype != MLT_FP16) return MLT_ERR_INVALID_ARG;
   if (B < 0 || H < 0 || Sq < 0 || Sk < 0 || D <= 0) return MLT_ERR_INVALID_ARG;
-  if (!(scale == scale)) return MLT_ERR_INVALID_ARG;     // NaN
+  if (!(scale == scale) || scale - scale != 0.f) return MLT_ERR_INVALID_ARG;   // NaN or infinite
   if (D != 64 && D != 128) return MLT_ERR_UNSUPPORTED;
   if (B == 0 || H == 0 || Sq == 0) return MLT_OK;
   if (Sk < 1) return MLT_ERR_INVALID_ARG;

@@ -1,0 +1,88 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/mlt.h declares, rejects
+bad arguments before touching a device, and answers the host-side tiling query. No kernel runs."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mlt.h")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2503_14985_amd import binding as b
+    return b
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mlt_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(binding):
+    names = declared_functions()
+    assert {"mlt_gemm", "mlt_mha_fwd", "mlt_status_string", "mlt_version"} <= set(names)
+    lib = binding.raw()
+    for n in names:
+        assert hasattr(lib, n), "libmlt.so does not export %s" % n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_status_strings_and_version(binding):
+    assert binding.mlt_status_string(0) == "ok"
+    seen = {binding.mlt_status_string(c) for c in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5
+    assert binding.mlt_status_string(-99) == "unknown status"
+    assert re.fullmatch(r"\d+\.\d+\.\d+", binding.mlt_version())
+
+
+def test_gemm_argument_validation_without_device(binding):
+    lib = binding.raw()
+    p = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    null = ctypes.c_void_p(0)
+    g = lib.mlt_gemm
+    assert g(-1, 8, 8, p, 8, p, 8, 0, p, 8, 0, None) == binding.MLT_ERR_INVALID_ARG
+    assert g(8, 8, 8, p, 8, p, 8, 0, p, 8, 7, None) == binding.MLT_ERR_INVALID_ARG      # dtype
+    assert g(8, 8, 8, null, 8, p, 8, 0, p, 8, 0, None) == binding.MLT_ERR_INVALID_ARG   # A null
+    assert g(8, 8, 8, p, 8, p, 8, 0, null, 8, 0, None) == binding.MLT_ERR_INVALID_ARG   # C null
+    assert g(8, 8, 16, p, 8, p, 8, 0, p, 8, 0, None) == binding.MLT_ERR_INVALID_ARG     # lda < K
+    assert g(8, 16, 8, p, 8, p, 8, 0, p, 16, 0, None) == binding.MLT_ERR_INVALID_ARG    # ldb < N
+    assert g(8, 16, 8, p, 8, p, 4, 1, p, 16, 0, None) == binding.MLT_ERR_INVALID_ARG    # ldb < K (transB)
+    assert g(8, 16, 8, p, 8, p, 16, 0, p, 8, 0, None) == binding.MLT_ERR_INVALID_ARG    # ldc < N
+    assert g(0, 16, 8, null, 8, null, 16, 0, null, 16, 0, None) == binding.MLT_OK       # M = 0: no-op
+    assert g(8, 0, 8, null, 8, null, 16, 0, null, 16, 1, None) == binding.MLT_OK        # N = 0: no-op
+
+
+def test_mha_argument_validation_without_device(binding):
+    lib = binding.raw()
+    p = ctypes.c_void_p(0x1000)
+    f = lib.mlt_mha_fwd
+    assert f(1, 1, 4, 4, 96, p, p, p, p, 1.0, 0, 0, None) == binding.MLT_ERR_UNSUPPORTED   # D
+    assert f(1, 1, 4, 0, 64, p, p, p, p, 1.0, 0, 0, None) == binding.MLT_ERR_INVALID_ARG   # Sk = 0
+    assert f(1, 1, 4, 4, 64, p, p, p, p, float("nan"), 0, 0, None) == binding.MLT_ERR_INVALID_ARG
+    assert f(1, 1, 4, 4, 64, p, p, p, p, float("inf"), 0, 0, None) == binding.MLT_ERR_INVALID_ARG
+    assert f(1, 1, 4, 4, 64, p, p, p, p, 1.0, 0, 5, None) == binding.MLT_ERR_INVALID_ARG   # dtype
+    assert f(1, 1, 4, 4, 64, ctypes.c_void_p(0), p, p, p, 1.0, 0, 0, None) == binding.MLT_ERR_INVALID_ARG
+    assert f(1, 1, 4, 4, 64, ctypes.c_void_p(0x1008), p, p, p, 1.0, 0, 0, None) == binding.MLT_ERR_INVALID_ARG  # alignment
+    assert f(0, 1, 4, 4, 64, p, p, p, p, 1.0, 0, 0, None) == binding.MLT_OK                # B = 0
+    assert f(1, 1, 0, 4, 128, p, p, p, p, 1.0, 1, 1, None) == binding.MLT_OK               # Sq = 0
+
+
+def test_tiling_query_is_the_papers_partition_rule(binding):
+    """The kernels' fixed layouts follow the paper's encoding rule (Section 2.1):
+    sizePerWarp = workgroupSize / warpsPerCTA, GEMM partitioned over both dimensions of the tile,
+    attention along the rows only (Section 2.5: warpsPerCTA = [numWarps, 1])."""
+    t = binding.mlt_query_tiling(0, (8192, 8192, 8192, 0), 0)
+    wg, waves, per_wave, mfma = t[0:2], t[2:4], t[4:6], t[6:9]
+    assert wg == [256, 256] and waves[0] * waves[1] == 8
+    assert per_wave == [wg[0] // waves[0], wg[1] // waves[1]]
+    assert mfma == [32, 32, 16] and per_wave[0] % 32 == 0 and per_wave[1] % 32 == 0
+    small = binding.mlt_query_tiling(0, (512, 512, 512, 1), 1)
+    assert small[0:2] == [128, 128]
+    a = binding.mlt_query_tiling(1, (4096, 4096, 128, 0), 0)
+    assert a[2:4] == [8, 1] and a[4] == a[0] // 8 and a[5] == 128 and a[9] == 64
+    with pytest.raises(binding.MltError):
+        binding.mlt_query_tiling(1, (4096, 4096, 80, 0), 0)
