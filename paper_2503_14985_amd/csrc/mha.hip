@@ -166,10 +166,36 @@ __global__ __launch_bounds__(MHA_NT) void mha_fwd_kernel(
   float m_run = -__builtin_inff();   // running maximum of the raw (unscaled, sign-adjusted) scores
   float l_run = 0.f;                 // running sum over this lane's half of the keys
 
+  // K fragments are fetched in chunks of KCH slices, one chunk ahead of the MFMAs that use them;
+  // V^T fragments per group of 16 keys (NDT MFMAs), one group ahead.
+  constexpr int KCH = 4;
+  constexpr int CPK = NKK / KCH;          // chunks per 32-key sub-tile
+  constexpr int NKC = 2 * CPK;            // chunks per key tile
+  static_assert(NKK % KCH == 0 && NKC % 2 == 0, "chunking of the first product");
+  auto load_kchunk = [&](const char* st, int ch, V8 (&kf)[KCH]) {
+    const int kb = ch / CPK, kk0 = (ch % CPK) * KCH;
+#pragma unroll
+    for (int i = 0; i < KCH; ++i)
+      kf[i] = lds_read8<V8>(st, k_frag + (kb * 32 * L::KSTR + (kk0 + i) * 16) * 2);
+  };
+  auto load_vgroup = [&](const char* st, int g, V8 (&vf)[NDT]) {
+    const int vrow = g * 16 * L::VSTR * 2;                 // keys 16*g .. 16*g + 15 of the tile
+#pragma unroll
+    for (int t = 0; t < NDT; ++t) {
+      const int off = v_frag + vrow + t * 32 * 2;
+      const s16x4 lo = lds_read_tr4(st, off);
+      const s16x4 hi = lds_read_tr4(st, off + 8 * L::VSTR * 2);
+      vf[t] = join_tr<V8>(lo, hi);
+    }
+  };
+
   load_kv(0);
   store_kv(0);
   if (nblk > 1) load_kv(1);
   __syncthreads();
+
+  V8 kf[2][KCH], vf[2][NDT];
+  load_kchunk(smem, 0, kf[0]);
 
   for (int j = 0; j < nblk; ++j) {
     const int cur = j & 1;
@@ -182,14 +208,18 @@ __global__ __launch_bounds__(MHA_NT) void mha_fwd_kernel(
     if (active) {
       // ---- S^T = K_j Q^T  (two 32-key sub-tiles)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_acc[kb][r] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) {
-          const V8 kf = lds_read8<V8>(st, k_frag + (kb * 32 * L::KSTR + kk * 16) * 2);
-          s_acc[kb] = mfma32(kf, qf[kk], s_acc[kb]);
-        }
+      for (int ch = 0; ch < NKC; ++ch) {
+        if (ch + 1 < NKC) load_kchunk(st, ch + 1, kf[(ch + 1) & 1]);
+        else load_vgroup(st, 0, vf[0]);                    // first V group rides along
+        __builtin_amdgcn_sched_barrier(0);
+        const int kb = ch / CPK, kk0 = (ch % CPK) * KCH;
+#pragma unroll
+        for (int i = 0; i < KCH; ++i) s_acc[kb] = mfma32(kf[ch & 1][i], qf[kk0 + i], s_acc[kb]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 
@@ -210,20 +240,14 @@ __global__ __launch_bounds__(MHA_NT) void mha_fwd_kernel(
       }
       // register r of sub-tile kb is key kb0 + 32*kb + 8*(r/4) + 4*h + r%4
       const bool need_mask = (CAUSAL && (kb0 + MHA_BN - 1 > q0)) || (kb0 + MHA_BN > Sk);
-      unsigned vis[2] = {0xffffu, 0xffffu};
+      const int limit = CAUSAL ? (my_q < Sk - 1 ? my_q : Sk - 1) : Sk - 1;     // last visible key
+      const int key_base = kb0 + 4 * h;
       if (need_mask) {
-        const int limit = CAUSAL ? (my_q < Sk - 1 ? my_q : Sk - 1) : Sk - 1;   // last visible key
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          unsigned bits = 0;
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kb0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-            if (key <= limit) bits |= 1u << r;
-            else s_acc[kb][r] = -__builtin_inff();
-          }
-          vis[kb] = bits;
-        }
+          for (int r = 0; r < 16; ++r)
+            if (key_base + 32 * kb + 8 * (r >> 2) + (r & 3) > limit) s_acc[kb][r] = -__builtin_inff();
       }
       float mx = s_acc[0][0];
 #pragma unroll
@@ -232,46 +256,58 @@ __global__ __launch_bounds__(MHA_NT) void mha_fwd_kernel(
         for (int r = 0; r < 16; ++r) mx = __builtin_fmaxf(mx, s_acc[kb][r]);
       mx = both_halves_max(mx);
       const float m_new = __builtin_fmaxf(m_run, mx);
-      const float alpha = (m_run == -__builtin_inff()) ? 0.f : __builtin_amdgcn_exp2f((m_run - m_new) * c);
-      const float mc = m_new * c;
+      // Rescale only when some row of this wavefront has a new maximum (alpha is 1 otherwise).
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+        const float alpha = (m_run == -__builtin_inff()) ? 0.f : __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        l_run *= alpha;
+#pragma unroll
+        for (int t = 0; t < NDT; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o_acc[t][r] *= alpha;
+        m_run = m_new;
+      }
+      const float mc = m_run * c;
       float psum = 0.f;
+      if (need_mask) {
+        // the exponent of a masked score may be NaN (c = 0): select the weight, never compute it
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r], c, -mc));
-          if (need_mask) p = ((vis[kb] >> r) & 1u) ? p : 0.f;
-          s_acc[kb][r] = p;
-          psum += p;
-        }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
-#pragma unroll
-      for (int t = 0; t < NDT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[t][r] *= alpha;
-
-      // ---- O^T += V_j^T P^T : per 16 keys one MFMA per 32-row tile of O^T
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int t16 = 0; t16 < 2; ++t16) {
-          u32x4 pw;
-#pragma unroll
-          for (int w = 0; w < 4; ++w)
-            pw[w] = Elem<Tag>::pack2(s_acc[kb][8 * t16 + 2 * w], s_acc[kb][8 * t16 + 2 * w + 1]);
-          const V8 pf = __builtin_bit_cast(V8, pw);
-          const int vrow = (kb * 32 + t16 * 16) * L::VSTR * 2;
-#pragma unroll
-          for (int t = 0; t < NDT; ++t) {
-            const int off = v_frag + vrow + t * 32 * 2;
-            const s16x4 lo = lds_read_tr4(st, off);
-            const s16x4 hi = lds_read_tr4(st, off + 8 * L::VSTR * 2);
-            o_acc[t] = mfma32(join_tr<V8>(lo, hi), pf, o_acc[t]);
+          for (int r = 0; r < 16; ++r) {
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r], c, -mc));
+            if (key_base + 32 * kb + 8 * (r >> 2) + (r & 3) > limit) p = 0.f;
+            s_acc[kb][r] = p;
+            psum += p;
           }
-        }
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r], c, -mc));
+            s_acc[kb][r] = p;
+            psum += p;
+          }
+      }
+      l_run += psum;
+
+      // ---- O^T += V_j^T P^T : per 16 keys (group g) one MFMA per 32-row tile of O^T
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        if (g + 1 < 4) load_vgroup(st, g + 1, vf[(g + 1) & 1]);
+        u32x4 pw;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          pw[w] = Elem<Tag>::pack2(s_acc[g >> 1][8 * (g & 1) + 2 * w], s_acc[g >> 1][8 * (g & 1) + 2 * w + 1]);
+        const V8 pf = __builtin_bit_cast(V8, pw);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NDT; ++t) o_acc[t] = mfma32(vf[g & 1][t], pf, o_acc[t]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     __syncthreads();
+    if (j + 1 < nblk) load_kchunk(smem + (cur ^ 1) * L::STAGE, 0, kf[0]);
   }
 
   // ---- epilogue: O = O^T / l, l summed over both key halves; 4 consecutive d per store
