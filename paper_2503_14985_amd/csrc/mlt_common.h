@@ -43,6 +43,12 @@ template <> struct Elem<bf16_tag> {
     bf16x2 h = __builtin_convertvector(v, bf16x2);
     return __builtin_bit_cast(uint32_t, h);
   }
+  // acc + lo + hi of a packed pair, exact in fp32 (v_dot2c_f32_bf16 against (1, 1))
+  static __device__ __forceinline__ float add_pair(uint32_t packed, float acc) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), ones, acc, false);
+  }
 };
 template <> struct Elem<f16_tag> {
   typedef f16x8 vec8;
@@ -56,6 +62,12 @@ template <> struct Elem<f16_tag> {
     f32x2 v = {lo, hi};
     f16x2 h = __builtin_convertvector(v, f16x2);
     return __builtin_bit_cast(uint32_t, h);
+  }
+  // acc + lo + hi of a packed pair (v_dot2c_f32_f16 against (1, 1))
+  static __device__ __forceinline__ float add_pair(uint32_t packed, float acc) {
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, packed), ones, acc, false);
   }
 };
 
