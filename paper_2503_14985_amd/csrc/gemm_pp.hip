@@ -1,0 +1,313 @@
+// GEMM C = A*B for gfx950, two-group ("ping-pong") schedule with direct global->LDS loads.
+//
+// Same three levels as the paper's GEMM (arXiv 2503.14985, Sections 2.1-2.3: workgroup tile,
+// per-warp sub-tile, hardware dot): workgroup tile 256 x 256, K step 64, 8 wavefronts as 2 x 4
+// owning 128 x 64 each, MFMA 32x32x16. What differs from gemm.hip is how memory traffic and
+// matrix work overlap. A CU runs one workgroup, two wavefronts per SIMD. The two wavefronts of a
+// SIMD are kept half a K step apart by one extra barrier at the start: while one of them issues
+// its 32 MFMAs of a K step back to back (compute phase), the other refills its operand fragments
+// from LDS for its next compute phase (memory phase). Every phase ends in a workgroup barrier, so
+// the matrix pipe of each SIMD always has exactly one wavefront feeding it and LDS latency never
+// sits in front of an MFMA.
+//
+// Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l of a
+// wavefront writes 16 bytes at base + 16*l). LDS (160 KB) is a ring of five 32 KB slots holding
+// the sequence A_0 B_0 A_1 B_1 A_2 ... (A_k, B_k: the operand tiles of K step k), i.e. two and a
+// half K steps. That extra half step is what lets every load be issued from a memory phase: the
+// vector memory path of a CU moves 64 bytes per clock, so the 64 KB of a K step occupy it for
+// half of the 2048 clocks the MFMAs of that step take, and a wavefront that issues loads in
+// front of its MFMAs stalls the matrix pipe. Group 1 fetches the A tiles, group 0 the B tiles.
+// Because the LDS side of such a
+// load is contiguous per wavefront, the tiles are stored unpadded and bank conflicts are avoided
+// by choosing WHICH 16-byte chunk of global memory each lane fetches (an XOR swizzle):
+//   A tile  [256 rows][8 chunks of 8 k]   chunk c of row r sits in slot c ^ ((r >> 1) & 7)
+//   B tile, B given as N x K: same as A with n as the row
+//   B tile, B given as K x N: [64 k][32 chunks of 8 n], chunk q of row k sits in slot q ^ 4*(k & 3)
+// With these, the 16 lanes that the LDS serves together hit 16 distinct 16-byte bank groups, for
+// the row reads (ds_read_b128) and for the transposing reads (ds_read_b64_tr_b16) alike.
+//
+// Requirements (checked by the host): K % 64 == 0, lda % 8 == 0, ldb % 8 == 0, N % 8 == 0 when B
+// is K x N, A and B 16-byte aligned, 256 * lda and 64 * ldb + N below 2^30 elements (32-bit
+// per-lane byte offsets). M and N need not be multiples of 256: out-of-range rows/columns are
+// clamped on load and never stored.
+#include "mlt_common.h"
+#include "mlt_internal.h"
+
+namespace mlt {
+
+namespace {
+
+constexpr int PP_BM = 256, PP_BN = 256, PP_BK = 64;
+constexpr int PP_NT = 512;
+constexpr int PP_A_BYTES = PP_BM * PP_BK * 2;            // 32 KB
+constexpr int PP_B_BYTES = PP_BN * PP_BK * 2;            // 32 KB
+constexpr int PP_SLOT = 32768;                           // one operand tile
+constexpr int PP_NSLOT = 5;
+constexpr int PP_SMEM = PP_NSLOT * PP_SLOT;              // 160 KB
+static_assert(PP_A_BYTES == PP_SLOT && PP_B_BYTES == PP_SLOT, "one tile per slot");
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
+constexpr int WAIT_LGKM0 = 0xC07F;       // lgkmcnt(0)
+constexpr int WAIT_VM0_LGKM0 = 0x0070;   // vmcnt(0) lgkmcnt(0)
+constexpr int WAIT_VM0 = 0x0F70;         // vmcnt(0)
+constexpr int WAIT_VM8 = 0x0F78;         // vmcnt(8)
+constexpr int WAIT_VM8_LGKM0 = 0x0078;   // vmcnt(8) lgkmcnt(0)
+
+__device__ __forceinline__ void tile_of_block_pp(int bid, int nbm, int nbn, int& tm, int& tn) {
+  constexpr int NXCD = 8, GROUP_M = 8;
+  const int total = nbm * nbn;
+  const int q = total / NXCD, rem = total % NXCD;
+  const int xcd = bid % NXCD, idx = bid / NXCD;
+  const int logical = xcd * q + (xcd < rem ? xcd : rem) + idx;
+  const int per_group = GROUP_M * nbn;
+  const int g = logical / per_group;
+  const int first_m = g * GROUP_M;
+  const int rows = (nbm - first_m) < GROUP_M ? (nbm - first_m) : GROUP_M;
+  const int in_g = logical % per_group;
+  tm = first_m + in_g % rows;
+  tn = in_g / rows;
+}
+
+// 16 bytes per lane from global memory (uniform base + per-lane byte offset) straight into LDS at
+// lds_addr + 16 * lane. Written as inline assembly on purpose: the compiler orders every LDS read
+// after a preceding LDS-writing load it knows of (s_waitcnt vmcnt(0)), which would serialise the
+// pipeline; here the ordering is established by the explicit waits and barriers of the schedule.
+__device__ __forceinline__ void load_lds16(const char* base, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(base)
+               : "memory", "m0");
+}
+
+}  // namespace
+
+template <typename Tag, bool TRANSB>
+__global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
+    int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
+    const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
+    int nbn) {
+  typedef typename Elem<Tag>::vec8 V8;
+  extern __shared__ __align__(16) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;               // 2 x 4 wavefronts of 128 x 64
+  const int grp = wm;                                    // waves 0-3 / 4-7: one of each per SIMD
+  int tile_m, tile_n;
+  tile_of_block_pp(blockIdx.x, nbm, nbn, tile_m, tile_n);
+  const int m0 = tile_m * PP_BM, n0 = tile_n * PP_BN;
+
+  // ---- global -> LDS assignments. A tile is 32 blocks of 1 KB (64 lanes x 16 bytes). The four
+  // wavefronts of group 1 fill the A tiles, those of group 0 the B tiles, 8 blocks each; lane l
+  // owns the 16-byte slot l of a block.
+  const char* ld_base;                                   // uniform: tile origin at k = 0
+  int64_t ld_kstep;                                      // uniform: bytes per K step
+  uint32_t voff[8];
+  if (grp == 1) {
+    ld_base = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
+    ld_kstep = PP_BK * 2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = ((wave & 3) * 8 + i) * 8 + (lane >> 3);   // tile row held by this slot
+      const int c = (lane & 7) ^ ((r >> 1) & 7);              // k chunk stored in this slot
+      const int rr = (m0 + r < M) ? r : (M - 1 - m0);
+      voff[i] = (uint32_t)rr * (uint32_t)lda * 2u + (uint32_t)c * 16u;
+    }
+  } else if (TRANSB) {
+    ld_base = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
+    ld_kstep = PP_BK * 2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = ((wave & 3) * 8 + i) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      const int rr = (n0 + r < N) ? r : (N - 1 - n0);
+      voff[i] = (uint32_t)rr * (uint32_t)ldb * 2u + (uint32_t)c * 16u;
+    }
+  } else {
+    ld_base = reinterpret_cast<const char*>(B);
+    ld_kstep = (int64_t)PP_BK * ldb * 2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int k = ((wave & 3) * 8 + i) * 2 + (lane >> 5);   // tile k row held by this slot
+      const int q = (lane & 31) ^ (4 * (k & 3));              // n chunk stored in this slot
+      const int col = n0 + q * 8;
+      voff[i] = (uint32_t)k * (uint32_t)ldb * 2u + (uint32_t)(col < N ? col : 0) * 2u;
+    }
+  }
+  const int KT = K / PP_BK;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;      // LDS byte address of the buffer
+  // this wavefront's 8 blocks of operand tile t (A_t for group 1, B_t for group 0) into a slot
+  auto issue_loads = [&](int t, int slot) {
+    const char* gp = ld_base + (int64_t)t * ld_kstep;
+    const uint32_t dst = lds0 + slot * PP_SLOT + (wave & 3) * 8192;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) load_lds16(gp, voff[i], dst + i * 1024);
+  };
+  // ---- fragment addresses inside a stage (per lane; tile and k slice offsets are immediates)
+  const int lq = lane & 31, h = lane >> 5;
+  int a_off[4], b_off[4];
+  {
+    const int r = wm * 128 + lq;
+    const int f = (lq >> 1) & 7;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) a_off[kk] = r * 128 + (((2 * kk + h) ^ f) * 16);
+  }
+  if (TRANSB) {
+    const int r = wn * 64 + lq;
+    const int f = (lq >> 1) & 7;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) b_off[kk] = r * 128 + (((2 * kk + h) ^ f) * 16);
+  } else {
+    // transposing read: 16-lane group g serves columns 16*(g%2).. of the 32-wide tile and k slots
+    // 8*(g/2)..; lane s of the group addresses k row s/4 (+4 for the second read), columns 4*(s%4)..
+    const int g = lane >> 4, s = lane & 15;
+    const int krow = 8 * (g >> 1) + (s >> 2);
+    const int q = wn * 8 + 2 * (g & 1) + ((s & 3) >> 1);
+    const int x = 4 * (s >> 2);
+    b_off[0] = krow * 512 + ((q ^ x) * 16) + 8 * (s & 1);        // column tile 0
+    b_off[1] = krow * 512 + (((q + 4) ^ x) * 16) + 8 * (s & 1);  // column tile 1
+    b_off[2] = b_off[3] = 0;
+  }
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  V8 af[4][4], bf[4][2];                                  // [k slice][tile]
+  auto read_frags = [&](const char* sa, const char* sb) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) af[kk][i] = lds_read8<V8>(sa, a_off[kk] + i * 32 * 128);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        if (TRANSB) {
+          bf[kk][j] = lds_read8<V8>(sb, b_off[kk] + j * 32 * 128);
+        } else {
+          const s16x4 lo = lds_read_tr4(sb, b_off[j] + kk * 16 * 512);
+          const s16x4 hi = lds_read_tr4(sb, b_off[j] + kk * 16 * 512 + 4 * 512);
+          bf[kk][j] = join_tr<V8>(lo, hi);
+        }
+      }
+    }
+  };
+
+
+  // Phase p ends at workgroup barrier p. Group 0 reads tile k (A_k and B_k) in phase 2k and
+  // multiplies in phase 2k+1; group 1 does the same one phase later. Operand tile number h
+  // (A_k: h = 2k, B_k: h = 2k+1) lives in slot h % 5 and is last read in phase 2k+1.
+  //   group 1, memory phase of step k (phase 2k+1): issues A_{k+2} into the slot B_{k-1} left in
+  //     phase 2k-1, then makes sure A_{k+1} (issued one step earlier) has landed: at most the 8
+  //     loads just issued may still be in flight;
+  //   group 0, memory phase of step k (phase 2k): issues B_{k+1} into the slot A_{k-1} left in
+  //     phase 2k-1, and waits for it at the end of its compute phase (phase 2k+1).
+  // Either way tile k+1 is complete when barrier 2k+1 releases, and its first reader (group 0,
+  // phase 2k+2) comes after that barrier.
+  if (grp == 1) {
+    issue_loads(0, 0);
+    if (KT > 1) { issue_loads(1, 2); __builtin_amdgcn_s_waitcnt(WAIT_VM8); }
+    else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+  } else {
+    issue_loads(0, 1);
+    if (KT > 1) { issue_loads(1, 3); __builtin_amdgcn_s_waitcnt(WAIT_VM8); }
+    else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+  }
+  __builtin_amdgcn_s_barrier();
+  if (grp == 1) __builtin_amdgcn_s_barrier();
+
+  int slot_a = 0;                                         // slot of A_k; B_k is in the next one
+  for (int k = 0; k < KT; ++k) {
+    const int slot_b = slot_a + 1 == PP_NSLOT ? 0 : slot_a + 1;
+    // ---- memory phase
+    read_frags(smem + slot_a * PP_SLOT, smem + slot_b * PP_SLOT);
+    __builtin_amdgcn_sched_barrier(0);
+    if (grp == 1) {
+      if (k + 2 < KT) {
+        issue_loads(k + 2, slot_a + 4 >= PP_NSLOT ? slot_a + 4 - PP_NSLOT : slot_a + 4);
+        __builtin_amdgcn_s_waitcnt(WAIT_VM8_LGKM0);
+      } else {
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0_LGKM0);
+      }
+    } else {
+      if (k >= 1 && k + 1 < KT)
+        issue_loads(k + 1, slot_a + 3 >= PP_NSLOT ? slot_a + 3 - PP_NSLOT : slot_a + 3);
+      __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+    }
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- compute phase
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32(af[kk][i], bf[kk][j], acc[i][j]);
+    __builtin_amdgcn_sched_barrier(0);
+    if (grp == 0) __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    slot_a = slot_a + 2 >= PP_NSLOT ? slot_a + 2 - PP_NSLOT : slot_a + 2;
+  }
+  if (grp == 0) __builtin_amdgcn_s_barrier();
+
+  // ---- epilogue: fp32 -> 16-bit (RNE), guarded element stores
+  const int row_base = m0 + wm * 128 + 4 * h;
+  const int col_base = n0 + wn * 64 + lq;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = col_base + j * 32;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+        if (row < M && col < N) C[(int64_t)row * ldc + col] = Elem<Tag>::from_f32(acc[i][j][r]);
+      }
+    }
+}
+
+bool gemm_pp_ok(const GemmArgs& g) {
+  auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  if (!al16(g.A) || !al16(g.B)) return false;
+  if (g.K < PP_BK || g.K % PP_BK || g.lda % 8 || g.ldb % 8) return false;
+  if (!g.transB && g.N % 8) return false;
+  const int64_t lim = (int64_t)1 << 30;
+  if (256 * g.lda >= lim) return false;
+  if (g.transB ? 256 * g.ldb >= lim : 64 * g.ldb + g.N >= lim) return false;
+  return true;
+}
+
+template <typename Tag, bool TRANSB>
+static int launch_pp(const GemmArgs& g, hipStream_t s) {
+  auto kern = gemm_pp_kernel<Tag, TRANSB>;
+  static thread_local int configured_dev = -1;          // opt in to > 64 KB LDS once per device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
+  if (configured_dev != dev) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            PP_SMEM) != hipSuccess) {
+      (void)hipGetLastError();
+      return MLT_ERR_LAUNCH;
+    }
+    configured_dev = dev;
+  }
+  const int nbm = (int)((g.M + PP_BM - 1) / PP_BM), nbn = (int)((g.N + PP_BN - 1) / PP_BN);
+  hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(PP_NT), PP_SMEM, s, (int)g.M, (int)g.N, (int)g.K,
+                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn);
+  return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
+}
+
+int run_gemm_pp(const GemmArgs& g, hipStream_t s) {
+  if (g.dtype == MLT_BF16)
+    return g.transB ? launch_pp<bf16_tag, true>(g, s) : launch_pp<bf16_tag, false>(g, s);
+  return g.transB ? launch_pp<f16_tag, true>(g, s) : launch_pp<f16_tag, false>(g, s);
+}
+
+}  // namespace mlt

@@ -29,7 +29,7 @@ bool device_is_gfx950() {
 }
 
 int forced_gemm_variant() {
-  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 256w8 | 256w8t.
+  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 256w8 | 256w8t | 256pp.
   const char* e = getenv("MLT_GEMM_VARIANT");
   if (!e || !*e) return GEMM_AUTO;
   if (!strcmp(e, "general")) return GEMM_GENERAL;
@@ -37,6 +37,7 @@ int forced_gemm_variant() {
   if (!strcmp(e, "128")) return GEMM_128;
   if (!strcmp(e, "256w8")) return GEMM_256_W8;
   if (!strcmp(e, "256w8t")) return GEMM_256_W8T;
+  if (!strcmp(e, "256pp")) return GEMM_256_PP;
   return GEMM_AUTO;
 }
 

@@ -12,6 +12,7 @@ enum GemmVariant {
   GEMM_128 = 3,       // 128x128x64, 4 wavefronts (2x2) of 64x64
   GEMM_256_W8 = 4,    // 256x256x64, 8 wavefronts (2x4) of 128x64
   GEMM_256_W8T = 5,   // 256x256x64, 8 wavefronts (4x2) of 64x128
+  GEMM_256_PP = 6,    // 256x256x64, 8 wavefronts (2x4), two-group schedule, direct-to-LDS loads
   GEMM_NUM_VARIANTS
 };
 
@@ -32,6 +33,8 @@ struct GemmPlan {
 
 GemmPlan plan_gemm(const GemmArgs& g);
 int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s);
+bool gemm_pp_ok(const GemmArgs& g);            // gemm_pp.hip: can the two-group kernel take this problem?
+int run_gemm_pp(const GemmArgs& g, hipStream_t s);
 
 struct MhaArgs {
   int64_t B, H, Sq, Sk, D;

@@ -51,6 +51,16 @@ def test_exact_tiles(variant, transB):
     _go(512, 768, 256, BF16, transB, variant=variant, seed=2)
 
 
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+@pytest.mark.parametrize("shape", [(520, 776, 320), (512, 768, 256), (100, 40, 64), (257, 264, 128)])
+def test_two_group_kernel(shape, transB, dtype):
+    # the direct-to-LDS two-group kernel: K a multiple of 64, ragged and exact M/N, one and many K steps
+    M, N, K = shape
+    name, _ = _go(M, N, K, dtype, transB, variant="256pp", seed=6)
+    assert name.endswith("_pp")
+
+
 @pytest.mark.parametrize("shape", [(1, 1, 1), (37, 53, 29), (65, 63, 33), (16, 8, 8), (8, 16, 24),
                                    (255, 257, 64), (3, 1000, 2048)])
 @pytest.mark.parametrize("transB", [False, True])
