@@ -21,6 +21,9 @@
 // the rescale of O^T by alpha is a plain per-lane multiply.
 //
 // Workgroup: 8 wavefronts x 32 query rows = 256 rows of one (batch, head); key tile 64.
+#include <stdlib.h>
+#include <string.h>
+
 #include "mlt_common.h"
 #include "mlt_internal.h"
 
@@ -366,12 +369,21 @@ MhaPlan plan_mha(const MhaArgs& a) {
   if (a.D != 64 && a.D != 128) return p;
   p.supported = true;
   p.bm = MHA_BM; p.bn = MHA_BN; p.waves = MHA_NW;
+  // Tuning/debug override: MLT_MHA_VARIANT = single selects the older single-schedule kernel.
+  const char* e = getenv("MLT_MHA_VARIANT");
+  p.two_group = mha_pp_ok(a) && !(e && !strcmp(e, "single"));
+  if (p.two_group) {
+    if (a.D == 128) p.name = a.causal ? "mha_fwd_d128_causal_256x64_pp" : "mha_fwd_d128_256x64_pp";
+    else p.name = a.causal ? "mha_fwd_d64_causal_256x64_pp" : "mha_fwd_d64_256x64_pp";
+    return p;
+  }
   if (a.D == 128) p.name = a.causal ? "mha_fwd_d128_causal_256x64" : "mha_fwd_d128_256x64";
   else p.name = a.causal ? "mha_fwd_d64_causal_256x64" : "mha_fwd_d64_256x64";
   return p;
 }
 
-int run_mha(const MhaArgs& a, const MhaPlan&, hipStream_t s) {
+int run_mha(const MhaArgs& a, const MhaPlan& p, hipStream_t s) {
+  if (p.two_group) return run_mha_pp(a, s);
   return a.dtype == MLT_BF16 ? run_mha_t<bf16_tag>(a, s) : run_mha_t<f16_tag>(a, s);
 }
 

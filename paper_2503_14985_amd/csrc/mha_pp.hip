@@ -1,0 +1,478 @@
+// Attention forward O = softmax(scale * Q K^T [+ causal mask]) V for gfx950, two-group schedule.
+//
+// The algorithm is the FlashAttention-2 forward of the paper (arXiv 2503.14985, Section 2.5,
+// Algorithm 1): Q is loaded once, K/V tiles stream through the loop, the two products sit back to
+// back with an online softmax in between, and the output tile is split over the wavefronts along
+// its rows only (the paper's warpsPerCTA = [numWarps, 1]), so no softmax statistic ever crosses a
+// wavefront. As the paper's layout table (Table 5) asks, P goes from the first product into the
+// second without being redistributed; on CDNA4 that holds when both products are computed
+// transposed,
+//   S^T = K_j Q^T      MFMA A operand = K_j rows (LDS), B operand = Q^T (registers)
+//   O^T += V_j^T P^T   MFMA A operand = V_j^T (LDS, transposing read), B operand = P^T
+// because a 32x32 accumulator gives lane l one column (one query) and 16 rows (keys), which is
+// exactly what the B operand of the next MFMA wants. Row statistics are per lane: the row maximum
+// needs one exchange with lane l^32, the row sum none until the end.
+//
+// Schedule. Workgroup = 8 wavefronts x 32 query rows; key tile 64. A CU runs one workgroup, two
+// wavefronts per SIMD (wavefronts w and w+4). Per key tile j a wavefront alternates between
+//   X_j  the softmax of S_j on the vector ALU (exp2, max, sum, conversion to 16 bit), and
+//   C_j  32 MFMAs back to back: O^T += V_j^T P_j^T, then S_{j+1}^T = K_{j+1} Q^T,
+// and the two wavefronts of a SIMD are kept one phase apart by an extra barrier at the start, so
+// that the matrix pipe always has one wavefront feeding it while the other one does the
+// exponentials: the two kinds of work overlap instead of queueing behind each other. Every phase
+// ends in a workgroup barrier.
+//
+// K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4), into a ring of 5
+// slots (tile t in slot t % 5), fetched three tiles ahead. The tiles are stored unpadded; bank
+// conflicts are avoided by choosing which 16-byte chunk each lane fetches (XOR swizzles, below).
+#include "mlt_common.h"
+#include "mlt_internal.h"
+
+namespace mlt {
+
+namespace {
+
+constexpr int PA_BM = 256;    // query rows per workgroup
+constexpr int PA_BN = 64;     // keys per tile
+constexpr int PA_NT = 512;
+constexpr int PA_NS = 5;      // LDS ring slots
+constexpr int PA_AHEAD = 3;
+constexpr float PA_LAZY_T = 8.f;   // log2 units a row maximum may grow before the reference point moves   // tiles fetched ahead of the softmax phase that issues the fetch
+
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
+constexpr int wait_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
+
+// 16 bytes per lane from global memory (uniform base + per-lane byte offset) straight into LDS at
+// lds_addr + 16 * lane. Inline assembly on purpose: the compiler would order every later LDS read
+// behind such a load (s_waitcnt vmcnt(0)); here the schedule's explicit waits and barriers do it.
+__device__ __forceinline__ void load_lds16(const void* base, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(base)
+               : "memory", "m0");
+}
+
+// max / sum of a per-lane value with the one held by lane l ^ 32 (the other half of the keys of
+// the same query): permlane32_swap fed the same register twice returns both halves' values.
+__device__ __forceinline__ float both_halves_max(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __builtin_fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+}
+__device__ __forceinline__ float both_halves_sum(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
+}
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  return __builtin_fmaxf(__builtin_fmaxf(a, b), c);       // v_max3_f32
+}
+
+// Workgroup id -> (batch*head, query tile): undo the round-robin of ids over the 8 XCDs so each
+// XCD owns a contiguous range, then walk the query tiles of one head, last tile first (with the
+// causal mask it has the most work). All tiles of a head share one XCD's L2.
+__device__ __forceinline__ void block_map(int bid, int total, int nq, int& bh, int& qt) {
+  constexpr int NXCD = 8;
+  const int q = total / NXCD, rem = total % NXCD;
+  const int xcd = bid % NXCD, idx = bid / NXCD;
+  const int logical = xcd * q + (xcd < rem ? xcd : rem) + idx;
+  bh = logical / nq;
+  qt = nq - 1 - logical % nq;
+}
+
+template <int D> struct PaCfg {
+  static constexpr int ROWB = D * 2;               // bytes per key row
+  static constexpr int TILE_B = PA_BN * ROWB;      // one K or V tile
+  static constexpr int SLOT_B = 2 * TILE_B;        // K tile then V tile
+  static constexpr int SMEM = PA_NS * SLOT_B;      // 160 KB (D = 128) / 80 KB (D = 64)
+  static constexpr int CPR = D / 8;                // 16-byte chunks per row
+  static constexpr int RPB = 64 / CPR;             // rows per 1 KB block (one wavefront load)
+  static constexpr int NBLK = PA_BN / RPB;         // blocks per tile
+  static constexpr int LPW = NBLK / 8;             // loads per wavefront per tile and matrix
+  static constexpr int NKK = D / 16;               // k slices of S^T = K Q^T
+  static constexpr int NDT = D / 32;               // 32-row tiles of O^T
+  // Swizzles. K rows are read 16 at a time at one chunk position (ds_read_b128), V rows 4 at a
+  // time over 4 adjacent chunks (ds_read_b64_tr_b16); each must cover 16 distinct bank groups.
+  static __device__ __forceinline__ int fk(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+  static __device__ __forceinline__ int fv(int row) { return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1); }
+};
+
+template <typename Tag, int D, bool CAUSAL>
+__global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+    const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int Sq, int Sk, int nq, int total,
+    float c, int negate) {
+  typedef PaCfg<D> L;
+  typedef typename Elem<Tag>::vec8 V8;
+  constexpr int NKK = L::NKK, NDT = L::NDT, ROWB = L::ROWB;
+  extern __shared__ __align__(16) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;                             // waves w and w+4 share a SIMD
+  const int lq = lane & 31, h = lane >> 5;
+  int bh, qt;
+  block_map(blockIdx.x, total, nq, bh, qt);
+  const int q0 = qt * PA_BM + wave * 32;                 // first query row of this wavefront
+  const int my_q = q0 + lq;
+
+  const uint16_t* Qh = Q + (int64_t)bh * Sq * D;
+  const char* Kh = reinterpret_cast<const char*>(K + (int64_t)bh * Sk * D);
+  const char* Vh = reinterpret_cast<const char*>(V + (int64_t)bh * Sk * D);
+
+  // Keys this workgroup looks at. Causal, top-left aligned: key j is visible to query i iff
+  // j <= i, so nothing beyond the last query row of the tile is needed.
+  int kv_len = Sk;
+  if (CAUSAL) {
+    const int last_q = (qt + 1) * PA_BM < Sq ? (qt + 1) * PA_BM : Sq;      // exclusive
+    kv_len = last_q < Sk ? last_q : Sk;
+  }
+  const int nblk = (kv_len + PA_BN - 1) / PA_BN;
+  // Causal: this wavefront has visible keys in tiles 0 .. my_nblk-1 only.
+  int my_nblk = nblk;
+  if (CAUSAL) {
+    const int need = (q0 + 31) / PA_BN + 1;
+    my_nblk = need < nblk ? need : nblk;
+  }
+
+  // ---- Q^T operand, resident in registers: query lq, d = 16*kk + 8*h .. +7. A negative scale is
+  // applied as a sign flip of Q (exact), so the softmax below always sees c >= 0.
+  V8 qf[NKK];
+  {
+    const int row = my_q < Sq ? my_q : Sq - 1;
+    const uint16_t* qp = Qh + (int64_t)row * D + 8 * h;
+    const uint32_t flip = negate ? 0x80008000u : 0u;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      u32x4 raw = *reinterpret_cast<const u32x4_mem*>(qp + kk * 16);
+      raw[0] ^= flip; raw[1] ^= flip; raw[2] ^= flip; raw[3] ^= flip;
+      qf[kk] = __builtin_bit_cast(V8, raw);
+    }
+  }
+
+  // ---- global -> LDS assignments: wavefront w fills blocks w*LPW .. of the K tile and of the V
+  // tile; lane l owns the 16-byte slot l of a block.
+  uint32_t voff_k[L::LPW], voff_v[L::LPW];
+  int ld_row[L::LPW];
+#pragma unroll
+  for (int i = 0; i < L::LPW; ++i) {
+    const int row = (wave * L::LPW + i) * L::RPB + lane / L::CPR;
+    const int slot = lane % L::CPR;
+    ld_row[i] = row;
+    voff_k[i] = (uint32_t)row * ROWB + (uint32_t)(slot ^ L::fk(row)) * 16u;
+    voff_v[i] = (uint32_t)row * ROWB + (uint32_t)(slot ^ L::fv(row)) * 16u;
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+  auto issue_tile = [&](int t) {
+    const uint32_t dst = lds0 + (t % PA_NS) * L::SLOT_B + wave * L::LPW * 1024;
+    const char* kp = Kh + (int64_t)t * L::TILE_B;
+    const char* vp = Vh + (int64_t)t * L::TILE_B;
+    if ((t + 1) * PA_BN <= Sk) {
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) load_lds16(kp, voff_k[i], dst + i * 1024);
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) load_lds16(vp, voff_v[i], dst + L::TILE_B + i * 1024);
+    } else {
+      // ragged last tile: rows past Sk re-read row Sk-1 (their weights are forced to 0)
+      const int last = Sk - 1 - t * PA_BN;
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) {
+        const int back = ld_row[i] > last ? (ld_row[i] - last) * ROWB : 0;
+        load_lds16(kp, voff_k[i] - back, dst + i * 1024);
+      }
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) {
+        const int back = ld_row[i] > last ? (ld_row[i] - last) * ROWB : 0;
+        load_lds16(vp, voff_v[i] - back, dst + L::TILE_B + i * 1024);
+      }
+    }
+  };
+
+  // ---- fragment addresses inside a slot
+  // K rows as MFMA A operand: key row lq of a 32-key sub-tile, chunk 2*kk + h, swizzled; the
+  // k slice enters by XOR (kk << 5 touches only chunk bits that 2*kk owns).
+  const int k_frag = lq * ROWB + ((h ^ L::fk(lq)) << 4);
+  // V^T as MFMA A operand through the transposing read: 16-lane group vg serves output rows
+  // d = 16*(vg%2) + i and contraction half vg/2; lane vs of the group addresses key row
+  // 4*(vg/2) + vs/4 (+8 for the second read) and d columns 4*(vs%4)..+3. The 32-row tile t of
+  // O^T enters by XOR (t << 6).
+  const int vg = lane >> 4, vs = lane & 15;
+  const int v_row = 4 * (vg >> 1) + (vs >> 2);
+  const int v_frag = L::TILE_B + v_row * ROWB + (((2 * (vg & 1) + ((vs & 3) >> 1)) ^ L::fv(v_row)) << 4) + 8 * (vs & 1);
+
+  f32x16 o_acc[NDT];
+#pragma unroll
+  for (int t = 0; t < NDT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o_acc[t][r] = 0.f;
+  f32x16 s_acc[2];
+  uint32_t pw[16];                   // P^T of the current tile, packed pairs
+  float mc_run = -__builtin_inff();  // running maximum of the scores, times c (log2 domain)
+  float l_run = 0.f;                 // running sum over this lane's half of the keys
+
+  // Operand fragments are fetched in chunks of NDT fragments (NDT MFMAs each). A compute phase
+  // runs 8 chunks: V_j groups 0..3 (16 keys each), then K_{j+1} chunks 0..3. Two chunk buffers;
+  // chunk n+2 is requested right after the MFMAs of chunk n have been issued.
+  V8 fb[2][NDT];
+  auto read_v_group = [&](const char* slot, int g, V8 (&f)[NDT]) {
+#pragma unroll
+    for (int t = 0; t < NDT; ++t) {
+      const int off = (v_frag ^ (t << 6)) + g * 16 * ROWB;
+      const s16x4 lo = lds_read_tr4(slot, off);
+      const s16x4 hi = lds_read_tr4(slot, off + 8 * ROWB);
+      f[t] = join_tr<V8>(lo, hi);
+    }
+  };
+  auto read_k_chunk = [&](const char* slot, int ch, V8 (&f)[NDT]) {
+#pragma unroll
+    for (int i = 0; i < NDT; ++i) {
+      const int fi = ch * NDT + i, kb = fi & 1, kk = fi >> 1;     // alternate the two accumulators
+      f[i] = lds_read8<V8>(slot, (k_frag ^ (kk << 5)) + kb * 32 * ROWB);
+    }
+  };
+  auto mfma_v_group = [&](int g, const V8 (&f)[NDT]) {
+    u32x4 p4 = {pw[4 * g], pw[4 * g + 1], pw[4 * g + 2], pw[4 * g + 3]};
+    const V8 pf = __builtin_bit_cast(V8, p4);
+#pragma unroll
+    for (int t = 0; t < NDT; ++t) o_acc[t] = mfma32(f[t], pf, o_acc[t]);
+  };
+  auto mfma_k_chunk = [&](int ch, const V8 (&f)[NDT]) {
+#pragma unroll
+    for (int i = 0; i < NDT; ++i) {
+      const int fi = ch * NDT + i, kb = fi & 1, kk = fi >> 1;     // alternate the two accumulators
+      s_acc[kb] = mfma32(f[i], qf[kk], s_acc[kb]);
+    }
+  };
+  auto zero_s = [&]() {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_acc[kb][r] = 0.f;
+  };
+
+  // ---- softmax of S_j (in s_acc) -> pw, l_run, mc_run, rescaled o_acc
+  auto softmax_tile = [&](int j) {
+    const int kb0 = j * PA_BN;
+    // register r of sub-tile kb is key kb0 + 32*kb + 8*(r/4) + 4*h + r%4
+    const bool need_mask = (CAUSAL && (kb0 + PA_BN - 1 > q0)) || (kb0 + PA_BN > Sk);
+    if (need_mask) {
+      // last visible key, relative to the first key this lane holds; a masked score becomes -inf
+      // (c > 0 always, see the launcher: its weight is then exactly exp2(-inf) = 0)
+      const int limit = CAUSAL ? (my_q < Sk - 1 ? my_q : Sk - 1) : Sk - 1;
+      const int rel = limit - (kb0 + 4 * h);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (32 * kb + 8 * (r >> 2) + (r & 3) > rel) s_acc[kb][r] = -__builtin_inff();
+    }
+    float mx = max3(s_acc[0][0], s_acc[0][1], s_acc[0][2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) mx = max3(mx, s_acc[0][r], s_acc[0][r + 1]);
+    mx = max3(mx, s_acc[0][15], s_acc[1][0]);
+#pragma unroll
+    for (int r = 1; r < 15; r += 2) mx = max3(mx, s_acc[1][r], s_acc[1][r + 1]);
+    mx = __builtin_fmaxf(mx, s_acc[1][15]);
+    mx = both_halves_max(mx);
+    // Lazy rescale: the reference point mc_run only moves when some row's maximum has grown by
+    // more than PA_LAZY_T in the log2 domain (weights then stay below 2^8, far inside fp32 and
+    // 16-bit range); mathematically the result does not depend on the reference point. The price:
+    // the largest weight of a row is no longer exactly 1, so it is rounded to 16 bit like the rest.
+    const float t = mx * c;
+    const bool grow = t - mc_run > PA_LAZY_T;                    // true on the first tile (mc_run = -inf)
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+      const float mc_new = grow ? t : mc_run;
+      const float alpha = grow ? __builtin_amdgcn_exp2f(mc_run - t) : 1.f;   // 0 on the first tile
+      l_run *= alpha;
+#pragma unroll
+      for (int tt = 0; tt < NDT; ++tt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[tt][r] *= alpha;
+      mc_run = mc_new;
+    }
+    {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r], c, -mc_run));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r + 1], c, -mc_run));
+          const uint32_t w = Elem<Tag>::pack2(p0, p1);
+          pw[8 * kb + r / 2] = w;
+          l_run = Elem<Tag>::add_pair(w, l_run);     // the sum of the ROUNDED weights, as used by P V
+        }
+    }
+  };
+
+  // ---- schedule
+  // Phase p ends at workgroup barrier p. Group 0: X_j in phase 2j, C_j in phase 2j+1; group 1 one
+  // phase later. Tile t is first read (K_t, by C_{t-1} of group 0) in phase 2t-1 and last read
+  // (V_t, by C_t of group 1) in phase 2t+2. In X_j every wavefront issues its share of tile j+3
+  // into the slot of tile j-2 (last read in phase 2j-2, before both groups' X_j) and then needs
+  // its share of tile j+1 complete before group 0's C_j (phase 2j+1) starts:
+  //   group 0 waits at the end of X_j (phase 2j) with the shares of tiles j+2, j+3 still in flight,
+  //   group 1 waits at the end of C_{j-1} (also phase 2j) with the share of tile j+2 in flight.
+  constexpr int LPT = 2 * L::LPW;                         // loads per wavefront per tile
+#pragma unroll
+  for (int t = 0; t < PA_AHEAD; ++t)
+    if (t < nblk) issue_tile(t);
+  // tile 0 (and with it K_0) must be complete for everyone: the prologue computes S_0
+  if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 15));
+  else if (nblk == 2) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+  else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+  __builtin_amdgcn_s_barrier();
+  if (grp == 1) __builtin_amdgcn_s_barrier();            // stagger: group 1 runs one phase behind
+
+  // prologue: S_0 = K_0 Q^T (a compute phase without the P V part)
+  {
+    const char* slot = smem;
+    zero_s();
+    if (my_nblk > 0) {
+      read_k_chunk(slot, 0, fb[0]);
+      read_k_chunk(slot, 1, fb[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_k_chunk(0, fb[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      read_k_chunk(slot, 2, fb[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_k_chunk(1, fb[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      read_k_chunk(slot, 3, fb[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_k_chunk(2, fb[0]);
+      mfma_k_chunk(3, fb[1]);
+    }
+    if (grp == 1) {
+      if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+      else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+    }
+    __builtin_amdgcn_s_barrier();
+  }
+
+  for (int j = 0; j < nblk; ++j) {
+    const char* slot = smem + (j % PA_NS) * L::SLOT_B;
+    const char* slot_next = smem + ((j + 1) % PA_NS) * L::SLOT_B;
+    const bool active = j < my_nblk;                       // wavefront-uniform
+    const bool active_next = j + 1 < my_nblk;
+    // ---- X_j
+    if (active) {
+      read_v_group(slot, 0, fb[0]);
+      read_v_group(slot, 1, fb[1]);
+    }
+    if (j + PA_AHEAD < nblk) issue_tile(j + PA_AHEAD);
+    __builtin_amdgcn_sched_barrier(0);
+    if (active) {
+      softmax_tile(j);
+      // keep the whole softmax on this side of the barrier (the weights are only consumed after it)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(pw[i]));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (grp == 0) {
+      // in flight, oldest first: tiles j+1, j+2, j+3 (those that exist)
+      const int newer = (j + 3 < nblk ? 1 : 0) + (j + 2 < nblk ? 1 : 0);
+      if (newer == 2) __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 0));
+      else if (newer == 1) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 0));
+      else __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+    } else {
+      __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
+    }
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- C_j: O^T += V_j^T P_j^T, then S_{j+1}^T = K_{j+1} Q^T. The order below is the
+    // schedule: the MFMAs of chunk n, then the LDS reads of chunk n+2 into the buffer just freed.
+#define MLT_STEP(mfma_stmt, read_stmt)      \
+  mfma_stmt;                                \
+  __builtin_amdgcn_sched_barrier(0);        \
+  read_stmt;                                \
+  __builtin_amdgcn_sched_barrier(0)
+    if (active) {
+      MLT_STEP(mfma_v_group(0, fb[0]), read_v_group(slot, 2, fb[0]));
+      MLT_STEP(mfma_v_group(1, fb[1]), read_v_group(slot, 3, fb[1]));
+      MLT_STEP(mfma_v_group(2, fb[0]), if (active_next) read_k_chunk(slot_next, 0, fb[0]));
+      MLT_STEP(mfma_v_group(3, fb[1]), if (active_next) read_k_chunk(slot_next, 1, fb[1]));
+    }
+    if (active_next) {
+      zero_s();
+      MLT_STEP(mfma_k_chunk(0, fb[0]), read_k_chunk(slot_next, 2, fb[0]));
+      MLT_STEP(mfma_k_chunk(1, fb[1]), read_k_chunk(slot_next, 3, fb[1]));
+      MLT_STEP(mfma_k_chunk(2, fb[0]), (void)0);
+      MLT_STEP(mfma_k_chunk(3, fb[1]), (void)0);
+    }
+#undef MLT_STEP
+    __builtin_amdgcn_sched_barrier(0);
+    if (grp == 1) {
+      // end of C_j = phase 2j+2 = the phase of group 0's X_{j+1}: tile j+2 must be complete;
+      // in flight behind it: tile j+3 (issued in X_j), if it exists
+      if (j + 3 < nblk) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+      else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+    }
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
+
+  // ---- epilogue: O = O^T / l, l summed over both key halves; 4 consecutive d per store
+  const float l_tot = both_halves_sum(l_run);
+  const float inv = 1.f / l_tot;
+  if (my_q < Sq) {
+    uint16_t* op = O + ((int64_t)bh * Sq + my_q) * D + 4 * h;
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 w;
+        w[0] = Elem<Tag>::pack2(o_acc[t][4 * g] * inv, o_acc[t][4 * g + 1] * inv);
+        w[1] = Elem<Tag>::pack2(o_acc[t][4 * g + 2] * inv, o_acc[t][4 * g + 3] * inv);
+        *reinterpret_cast<u32x2_mem*>(op + t * 32 + 8 * g) = w;
+      }
+  }
+}
+
+template <typename Tag, int D, bool CAUSAL>
+int launch_mha_pp(const MhaArgs& a, hipStream_t s) {
+  typedef PaCfg<D> L;
+  auto kern = mha_pp_kernel<Tag, D, CAUSAL>;
+  static thread_local int configured_dev = -1;          // opt in to > 64 KB LDS once per device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
+  if (configured_dev != dev) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            L::SMEM) != hipSuccess) {
+      (void)hipGetLastError();
+      return MLT_ERR_LAUNCH;
+    }
+    configured_dev = dev;
+  }
+  const int nq = (int)((a.Sq + PA_BM - 1) / PA_BM);
+  const int64_t total = a.B * a.H * nq;
+  if (total > 0x7fffffff) return MLT_ERR_UNSUPPORTED;
+  const float LOG2E = 1.4426950408889634f;
+  // c > 0 always: a zero scale becomes a positive one too small to move any weight off 1, which
+  // keeps (-inf) * c = -inf for masked scores instead of NaN
+  float c = (a.scale < 0 ? -a.scale : a.scale) * LOG2E;
+  if (c < 1e-30f) c = 1e-30f;
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(PA_NT), L::SMEM, s, a.Q, a.K, a.V, a.O,
+                     (int)a.Sq, (int)a.Sk, nq, (int)total, c, a.scale < 0 ? 1 : 0);
+  return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
+}
+
+template <typename Tag>
+int run_mha_pp_t(const MhaArgs& a, hipStream_t s) {
+  if (a.D == 128) return a.causal ? launch_mha_pp<Tag, 128, true>(a, s) : launch_mha_pp<Tag, 128, false>(a, s);
+  if (a.D == 64) return a.causal ? launch_mha_pp<Tag, 64, true>(a, s) : launch_mha_pp<Tag, 64, false>(a, s);
+  return MLT_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+// Sk * D * 2 must fit the 32-bit per-lane byte offsets of the direct loads.
+bool mha_pp_ok(const MhaArgs& a) { return (a.D == 64 || a.D == 128) && a.Sk * a.D * 2 < ((int64_t)1 << 31); }
+
+int run_mha_pp(const MhaArgs& a, hipStream_t s) {
+  return a.dtype == MLT_BF16 ? run_mha_pp_t<bf16_tag>(a, s) : run_mha_pp_t<f16_tag>(a, s);
+}
+
+}  // namespace mlt

@@ -48,7 +48,10 @@ struct MhaPlan {
   const char* name = "";
   int bm = 0, bn = 0, waves = 0;
   bool supported = false;
+  bool two_group = false;   // mha_pp.hip (default) or the single-schedule kernel of mha.hip
 };
+bool mha_pp_ok(const MhaArgs& a);
+int run_mha_pp(const MhaArgs& a, hipStream_t s);
 
 MhaPlan plan_mha(const MhaArgs& a);
 int run_mha(const MhaArgs& a, const MhaPlan& p, hipStream_t s);
