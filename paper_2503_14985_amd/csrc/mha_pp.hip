@@ -214,43 +214,38 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
 
   // Operand fragments are fetched in chunks of NDT fragments (NDT MFMAs each). A compute phase
   // runs 8 chunks: V_j groups 0..3 (16 keys each), then K_{j+1} chunks 0..3. Two chunk buffers;
-  // chunk n+2 is requested right after the MFMAs of chunk n have been issued.
+  // the fragment that will take a buffer entry next is requested right after the MFMA that read
+  // the entry has been issued, so between two MFMAs the wavefront issues at most two LDS reads
+  // and one address computation (which the 32 clocks of the running MFMA cover), and every
+  // request has about two chunks (2 * NDT MFMAs) of time to arrive.
   V8 fb[2][NDT];
-  auto read_v_group = [&](const char* slot, int g, V8 (&f)[NDT]) {
-#pragma unroll
-    for (int t = 0; t < NDT; ++t) {
-      const int off = (v_frag ^ (t << 6)) + g * 16 * ROWB;
-      const s16x4 lo = lds_read_tr4(slot, off);
-      const s16x4 hi = lds_read_tr4(slot, off + 8 * ROWB);
-      f[t] = join_tr<V8>(lo, hi);
-    }
+  // vb / kb: this lane's fragment address plus the slot offset (low bits of the slot offset are
+  // zero, so the XOR that selects the O^T tile / the k slice still only touches chunk bits)
+  auto read_v_frag = [&](int vb, int g, int t, V8& f) {
+    const int off = (vb ^ (t << 6)) + g * 16 * ROWB;
+    const s16x4 lo = lds_read_tr4(smem, off);
+    const s16x4 hi = lds_read_tr4(smem, off + 8 * ROWB);
+    f = join_tr<V8>(lo, hi);
   };
-  auto read_k_chunk = [&](const char* slot, int ch, V8 (&f)[NDT]) {
-#pragma unroll
-    for (int i = 0; i < NDT; ++i) {
-      const int fi = ch * NDT + i, kb = fi & 1, kk = fi >> 1;     // alternate the two accumulators
-      f[i] = lds_read8<V8>(slot, (k_frag ^ (kk << 5)) + kb * 32 * ROWB);
-    }
+  // K fragment fi of a tile: sub-tile fi & 1 (the two S^T accumulators alternate), k slice fi >> 1
+  auto read_k_frag = [&](int kb, int fi, V8& f) {
+    f = lds_read8<V8>(smem, (kb ^ ((fi >> 1) << 5)) + (fi & 1) * 32 * ROWB);
   };
-  auto mfma_v_group = [&](int g, const V8 (&f)[NDT]) {
+  auto mfma_v = [&](int g, int t, const V8& f) {
     u32x4 p4 = {pw[4 * g], pw[4 * g + 1], pw[4 * g + 2], pw[4 * g + 3]};
-    const V8 pf = __builtin_bit_cast(V8, p4);
-#pragma unroll
-    for (int t = 0; t < NDT; ++t) o_acc[t] = mfma32(f[t], pf, o_acc[t]);
+    o_acc[t] = mfma32(f, __builtin_bit_cast(V8, p4), o_acc[t]);
   };
-  auto mfma_k_chunk = [&](int ch, const V8 (&f)[NDT]) {
+  auto mfma_k = [&](int fi, const V8& f) {
+    if (fi < 2) {                                         // first slice: start from zero
+      f32x16 z;
 #pragma unroll
-    for (int i = 0; i < NDT; ++i) {
-      const int fi = ch * NDT + i, kb = fi & 1, kk = fi >> 1;     // alternate the two accumulators
-      s_acc[kb] = mfma32(f[i], qf[kk], s_acc[kb]);
+      for (int r = 0; r < 16; ++r) z[r] = 0.f;
+      s_acc[fi & 1] = mfma32(f, qf[fi >> 1], z);
+    } else {
+      s_acc[fi & 1] = mfma32(f, qf[fi >> 1], s_acc[fi & 1]);
     }
   };
-  auto zero_s = [&]() {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s_acc[kb][r] = 0.f;
-  };
+#define MLT_SB() __builtin_amdgcn_sched_barrier(0)
 
   // ---- softmax of S_j (in s_acc) -> pw, l_run, mc_run, rescaled o_acc
   auto softmax_tile = [&](int j) {
@@ -325,24 +320,25 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
   __builtin_amdgcn_s_barrier();
   if (grp == 1) __builtin_amdgcn_s_barrier();            // stagger: group 1 runs one phase behind
 
-  // prologue: S_0 = K_0 Q^T (a compute phase without the P V part)
+  // prologue: S_0 = K_0 Q^T, then the first two V_0 groups (a compute phase without the P V part)
   {
-    const char* slot = smem;
-    zero_s();
+    const int kb = k_frag, vb = v_frag;                   // slot 0
     if (my_nblk > 0) {
-      read_k_chunk(slot, 0, fb[0]);
-      read_k_chunk(slot, 1, fb[1]);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_k_chunk(0, fb[0]);
-      __builtin_amdgcn_sched_barrier(0);
-      read_k_chunk(slot, 2, fb[0]);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_k_chunk(1, fb[1]);
-      __builtin_amdgcn_sched_barrier(0);
-      read_k_chunk(slot, 3, fb[1]);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_k_chunk(2, fb[0]);
-      mfma_k_chunk(3, fb[1]);
+#pragma unroll
+      for (int i = 0; i < NDT; ++i) read_k_frag(kb, i, fb[0][i]);
+#pragma unroll
+      for (int i = 0; i < NDT; ++i) read_k_frag(kb, NDT + i, fb[1][i]);
+      MLT_SB();
+#pragma unroll
+      for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+        for (int i = 0; i < NDT; ++i) {
+          mfma_k(ch * NDT + i, fb[ch & 1][i]);
+          MLT_SB();
+          if (ch < 2) read_k_frag(kb, (ch + 2) * NDT + i, fb[ch & 1][i]);
+          else read_v_frag(vb, ch - 2, i, fb[ch & 1][i]);
+          MLT_SB();
+        }
     }
     if (grp == 1) {
       if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
@@ -351,16 +347,12 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
     __builtin_amdgcn_s_barrier();
   }
 
+  int slot_off = 0;                                       // byte offset of tile j's slot
   for (int j = 0; j < nblk; ++j) {
-    const char* slot = smem + (j % PA_NS) * L::SLOT_B;
-    const char* slot_next = smem + ((j + 1) % PA_NS) * L::SLOT_B;
+    const int slot_off_next = slot_off + L::SLOT_B == L::SMEM ? 0 : slot_off + L::SLOT_B;
     const bool active = j < my_nblk;                       // wavefront-uniform
     const bool active_next = j + 1 < my_nblk;
-    // ---- X_j
-    if (active) {
-      read_v_group(slot, 0, fb[0]);
-      read_v_group(slot, 1, fb[1]);
-    }
+    // ---- X_j (the first two V_j groups are already in the chunk buffers)
     if (j + PA_AHEAD < nblk) issue_tile(j + PA_AHEAD);
     __builtin_amdgcn_sched_barrier(0);
     if (active) {
@@ -381,27 +373,37 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
     }
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // ---- C_j: O^T += V_j^T P_j^T, then S_{j+1}^T = K_{j+1} Q^T. The order below is the
-    // schedule: the MFMAs of chunk n, then the LDS reads of chunk n+2 into the buffer just freed.
-#define MLT_STEP(mfma_stmt, read_stmt)      \
-  mfma_stmt;                                \
-  __builtin_amdgcn_sched_barrier(0);        \
-  read_stmt;                                \
-  __builtin_amdgcn_sched_barrier(0)
-    if (active) {
-      MLT_STEP(mfma_v_group(0, fb[0]), read_v_group(slot, 2, fb[0]));
-      MLT_STEP(mfma_v_group(1, fb[1]), read_v_group(slot, 3, fb[1]));
-      MLT_STEP(mfma_v_group(2, fb[0]), if (active_next) read_k_chunk(slot_next, 0, fb[0]));
-      MLT_STEP(mfma_v_group(3, fb[1]), if (active_next) read_k_chunk(slot_next, 1, fb[1]));
+    // ---- C_j: O^T += V_j^T P_j^T, then S_{j+1}^T = K_{j+1} Q^T, then the first two groups of
+    // V_{j+1} into the buffers for the next compute phase. Chunk n's MFMAs alternate with the
+    // reads of chunk n+2: V_j groups 2, 3, then K_{j+1} chunks 0..3, then V_{j+1} groups 0, 1.
+    {
+      const int vb = v_frag + slot_off;
+      const int kb = k_frag + slot_off_next, vbn = v_frag + slot_off_next;
+      if (active) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int t = 0; t < NDT; ++t) {
+            mfma_v(g, t, fb[g & 1][t]);
+            MLT_SB();
+            if (g < 2) read_v_frag(vb, g + 2, t, fb[g & 1][t]);
+            else if (active_next) read_k_frag(kb, (g - 2) * NDT + t, fb[g & 1][t]);
+            MLT_SB();
+          }
+      }
+      if (active_next) {
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+          for (int i = 0; i < NDT; ++i) {
+            mfma_k(ch * NDT + i, fb[ch & 1][i]);
+            MLT_SB();
+            if (ch < 2) read_k_frag(kb, (ch + 2) * NDT + i, fb[ch & 1][i]);
+            else read_v_frag(vbn, ch - 2, i, fb[ch & 1][i]);
+            MLT_SB();
+          }
+      }
     }
-    if (active_next) {
-      zero_s();
-      MLT_STEP(mfma_k_chunk(0, fb[0]), read_k_chunk(slot_next, 2, fb[0]));
-      MLT_STEP(mfma_k_chunk(1, fb[1]), read_k_chunk(slot_next, 3, fb[1]));
-      MLT_STEP(mfma_k_chunk(2, fb[0]), (void)0);
-      MLT_STEP(mfma_k_chunk(3, fb[1]), (void)0);
-    }
-#undef MLT_STEP
     __builtin_amdgcn_sched_barrier(0);
     if (grp == 1) {
       // end of C_j = phase 2j+2 = the phase of group 0's X_{j+1}: tile j+2 must be complete;
@@ -411,7 +413,9 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
     }
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+    slot_off = slot_off_next;
   }
+#undef MLT_SB
   if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
 
   // ---- epilogue: O = O^T / l, l summed over both key halves; 4 consecutive d per store
