@@ -29,7 +29,7 @@ bool device_is_gfx950() {
 }
 
 int forced_gemm_variant() {
-  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 256w8 | 256w8t | 256pp.
+  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 256w8 | 256w8t | 256pp | skinny.
   const char* e = getenv("MLT_GEMM_VARIANT");
   if (!e || !*e) return GEMM_AUTO;
   if (!strcmp(e, "general")) return GEMM_GENERAL;
@@ -38,6 +38,7 @@ int forced_gemm_variant() {
   if (!strcmp(e, "256w8")) return GEMM_256_W8;
   if (!strcmp(e, "256w8t")) return GEMM_256_W8T;
   if (!strcmp(e, "256pp")) return GEMM_256_PP;
+  if (!strcmp(e, "skinny")) return GEMM_SKINNY;
   return GEMM_AUTO;
 }
 
@@ -137,8 +138,8 @@ int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]) 
     GemmPlan p = plan_gemm(g);
     if (p.variant == GEMM_ZERO) { for (int i = 0; i < 10; ++i) out[i] = 0; return MLT_OK; }
     out[0] = p.bm; out[1] = p.bn; out[2] = p.wm; out[3] = p.wn;
-    out[4] = p.bm / p.wm; out[5] = p.bn / p.wn; out[6] = 32; out[7] = 32; out[8] = 16;
-    out[9] = p.bk;
+    out[4] = p.bm / p.wm; out[5] = p.bn / p.wn; out[6] = p.mfma_m; out[7] = p.mfma_n;
+    out[8] = p.mfma_k; out[9] = p.bk;
     return MLT_OK;
   }
   if (op == 1) {

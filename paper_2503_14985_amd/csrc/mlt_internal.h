@@ -13,6 +13,7 @@ enum GemmVariant {
   GEMM_256_W8 = 4,    // 256x256x64, 8 wavefronts (2x4) of 128x64
   GEMM_256_W8T = 5,   // 256x256x64, 8 wavefronts (4x2) of 64x128
   GEMM_256_PP = 6,    // 256x256x64, 8 wavefronts (2x4), two-group schedule, direct-to-LDS loads
+  GEMM_SKINNY = 7,    // M <= 64, B stored N x K: 16 columns per workgroup, K split over 8 wavefronts
   GEMM_NUM_VARIANTS
 };
 
@@ -29,12 +30,15 @@ struct GemmPlan {
   int variant = GEMM_GENERAL;
   const char* name = "";
   int bm = 0, bn = 0, bk = 0, wm = 0, wn = 0;
+  int mfma_m = 32, mfma_n = 32, mfma_k = 16;
 };
 
 GemmPlan plan_gemm(const GemmArgs& g);
 int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s);
 bool gemm_pp_ok(const GemmArgs& g);            // gemm_pp.hip: can the two-group kernel take this problem?
 int run_gemm_pp(const GemmArgs& g, hipStream_t s);
+bool gemm_skinny_ok(const GemmArgs& g);        // gemm_skinny.hip
+int run_gemm_skinny(const GemmArgs& g, hipStream_t s);
 
 struct MhaArgs {
   int64_t B, H, Sq, Sk, D;

@@ -61,6 +61,21 @@ def test_two_group_kernel(shape, transB, dtype):
     assert name.endswith("_pp")
 
 
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+@pytest.mark.parametrize("shape", [(16, 1024, 4096), (1, 1040, 512), (7, 1500, 264), (33, 2048, 8200),
+                                   (64, 1024, 1000), (48, 1031, 4096 + 32)])
+def test_skinny_kernel(shape, dtype):
+    # M <= 64 with B stored N x K: one to four 16-row tiles, ragged N, K with and without a partial
+    # last batch (K % 4096 != 0) and a partial last chunk (K % 32 != 0)
+    M, N, K = shape
+    name, _ = _go(M, N, K, dtype, True, std=0.02, seed=7)
+    assert "skinny" in name
+    # the same problem through the tile kernel must agree with the oracle too (and is what a
+    # row-major B or a larger M gets)
+    name, _ = _go(M, N, K, dtype, True, std=0.02, seed=7, variant="128")
+    assert "skinny" not in name
+
+
 @pytest.mark.parametrize("shape", [(1, 1, 1), (37, 53, 29), (65, 63, 33), (16, 8, 8), (8, 16, 24),
                                    (255, 257, 64), (3, 1000, 2048)])
 @pytest.mark.parametrize("transB", [False, True])
