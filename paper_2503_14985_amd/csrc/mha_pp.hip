@@ -373,6 +373,8 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
     }
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+    // (measured: with D = 128 the MFMA phase gains 3 % from a raised issue priority, D = 64 loses)
+    if (D == 128) __builtin_amdgcn_s_setprio(1);
     // ---- C_j: O^T += V_j^T P_j^T, then S_{j+1}^T = K_{j+1} Q^T, then the first two groups of
     // V_{j+1} into the buffers for the next compute phase. Chunk n's MFMAs alternate with the
     // reads of chunk n+2: V_j groups 2, 3, then K_{j+1} chunks 0..3, then V_{j+1} groups 0, 1.
@@ -404,6 +406,7 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
           }
       }
     }
+    if (D == 128) __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     if (grp == 1) {
       // end of C_j = phase 2j+2 = the phase of group 0's X_{j+1}: tile j+2 must be complete;
