@@ -93,6 +93,35 @@ def cpu_baseline(A, B, Q, K, V, scale):
     }
 
 
+def mfma_ceiling(binding, ev, A, dev):
+    """Rate of a register-only MFMA loop over the whole chip (mlt_probe_mfma) on all-zero operands
+    and on the GEMM's own N(0,1) operand values: the second is what the chip's power management
+    leaves of the nominal peak for such data, before any memory traffic. Context for `roofline`,
+    whose `peak` stays the nominal one."""
+    import torch
+    sink = torch.zeros(16, dtype=torch.float32, device=dev)
+    res = {}
+    for name, data in (("zeros", torch.zeros(1 << 16, dtype=torch.bfloat16, device=dev)),
+                       ("n01", A.reshape(-1)[: 1 << 16].contiguous())):
+        iters, reps = 2048, 12
+        for _ in range(3):
+            binding.mlt_probe_mfma(iters, data, sink)
+        e0, e1 = ev.create(), ev.create()
+        binding.mlt_set_timing_events(e0, None)
+        flop = binding.mlt_probe_mfma(iters, data, sink)
+        binding.mlt_set_timing_events(None, None)
+        for _ in range(reps - 2):
+            binding.mlt_probe_mfma(iters, data, sink)
+        binding.mlt_set_timing_events(None, e1)
+        binding.mlt_probe_mfma(iters, data, sink)
+        binding.mlt_set_timing_events(None, None)
+        torch.cuda.synchronize()
+        res[name + "_tflops"] = flop * reps / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e12
+    res["note"] = ("register-only bf16 32x32x16 MFMA loop, 8 wavefronts per CU; n01 = operands "
+                   "taken from the GEMM's A matrix")
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,6 +129,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle timing (used when profiling)")
+    ap.add_argument("--only", choices=["gemm", "mha"], default=None,
+                    help="run only one of the two kernels per step (for counter runs of one kernel)")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the measurement of the power-limited MFMA ceiling")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps also run plain device copies of 256 MiB, so a "
                          "counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) can be scaled by "
@@ -130,14 +163,17 @@ def main():
     pairs = [(ev.create(), ev.create(), ev.create(), ev.create()) for _ in range(args.steps)]
 
     def step(p=None):
-        if p is not None:
-            binding.mlt_set_timing_events(p[0], p[1])
-        binding.mlt_gemm(A, B, C=C)
-        gemm_name = binding.mlt_last_kernel()
-        if p is not None:
-            binding.mlt_set_timing_events(p[2], p[3])
-        binding.mlt_mha_fwd(Q, K, V, scale, causal=False, O=O)
-        mha_name = binding.mlt_last_kernel()
+        gemm_name = mha_name = ""
+        if args.only != "mha":
+            if p is not None:
+                binding.mlt_set_timing_events(p[0], p[1])
+            binding.mlt_gemm(A, B, C=C)
+            gemm_name = binding.mlt_last_kernel()
+        if args.only != "gemm":
+            if p is not None:
+                binding.mlt_set_timing_events(p[2], p[3])
+            binding.mlt_mha_fwd(Q, K, V, scale, causal=False, O=O)
+            mha_name = binding.mlt_last_kernel()
         if p is not None:
             binding.mlt_set_timing_events(None, None)
         return gemm_name, mha_name
@@ -157,6 +193,13 @@ def main():
         for _ in range(3):
             dst.copy_(src)          # reads 256 MiB, writes 256 MiB per launch
         torch.cuda.synchronize()
+
+    if args.only is not None:
+        # counter / trace runs of a single kernel: no JSON line, just the kernel's own time
+        which = 0 if args.only == "gemm" else 2
+        ms = [ev.elapsed_ms(p[which], p[which + 1]) for p in pairs]
+        print("%s: %s avg %.4f ms over %d launches" % (args.only, names[which // 2], sum(ms) / len(ms), len(ms)))
+        return
 
     gemm_ms = [ev.elapsed_ms(p[0], p[1]) for p in pairs]
     mha_ms = [ev.elapsed_ms(p[2], p[3]) for p in pairs]
@@ -194,6 +237,8 @@ def main():
                 "flop_convention": "4*B*H*Sq*Sk*D"},
         "roofline": roofline,
     }
+    if not args.no_ceiling:
+        out["mfma_ceiling"] = mfma_ceiling(binding, ev, A, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(A_h, B_h, Q_h, K_h, V_h, scale)
     print(json.dumps(out))

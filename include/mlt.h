@@ -76,6 +76,19 @@ int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const v
                 void* stream);
 
 /*
+ * Diagnostic for benchmarks (not part of the paper's method): enqueues one kernel in which every
+ * wavefront of the chip issues bf16 32x32x16 MFMAs back to back from registers, `iters` times 32
+ * of them, 8 wavefronts per CU. The rate it reaches is the practical MFMA ceiling FOR THE GIVEN
+ * OPERAND VALUES: the chip lowers its clock under the power that toggling operand bits costs.
+ *   data    device, at least 64 KiB, 16-byte aligned: the bf16 values used as operands
+ *   sink    device, at least 4 bytes (written practically never; keeps the loop alive)
+ *   flop    host, out: floating-point operations the launch executes (time it with events)
+ * Returns MLT_OK, MLT_ERR_INVALID_ARG (null pointer, iters outside 1 .. 2^20) or a launch/device
+ * error.
+ */
+int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* stream);
+
+/*
  * Per-kernel timing hook for benchmarks: when `start_event`/`stop_event` (hipEvent_t as void*,
  * may be NULL) are set, the next launches made by this thread record them on the launch stream
  * immediately before the first and after the last kernel of one entry-point call. Pass NULLs to

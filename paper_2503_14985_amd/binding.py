@@ -19,7 +19,7 @@ MLT_BF16, MLT_FP16 = 0, 1
 MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE = 0, -1, -2, -3, -4
 
 EXPORTS = ("mlt_gemm", "mlt_mha_fwd", "mlt_set_timing_events", "mlt_last_kernel",
-           "mlt_query_tiling", "mlt_status_string", "mlt_version")
+           "mlt_query_tiling", "mlt_status_string", "mlt_version", "mlt_probe_mfma")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -33,6 +33,8 @@ _lib.mlt_gemm.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, 
 _lib.mlt_mha_fwd.restype = _i32
 _lib.mlt_mha_fwd.argtypes = [_i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, ctypes.c_float, _i32,
                              _i32, _p]
+_lib.mlt_probe_mfma.restype = _i32
+_lib.mlt_probe_mfma.argtypes = [_i32, _p, _p, ctypes.POINTER(ctypes.c_double), _p]
 _lib.mlt_set_timing_events.restype = None
 _lib.mlt_set_timing_events.argtypes = [_p, _p]
 _lib.mlt_last_kernel.restype = ctypes.c_char_p
@@ -64,6 +66,19 @@ def mlt_version() -> str:
 
 def mlt_last_kernel() -> str:
     return _lib.mlt_last_kernel().decode()
+
+
+def mlt_probe_mfma(iters: int, data: torch.Tensor, sink: torch.Tensor) -> float:
+    """Enqueue the register-only MFMA loop on the current stream; returns the flop it executes.
+    `data`: at least 64 KiB of bf16 operand values on the GPU, `sink`: at least 4 bytes."""
+    if not data.is_cuda or data.numel() * data.element_size() < 65536 or not data.is_contiguous():
+        raise ValueError("mlt_probe_mfma: data must be a contiguous GPU tensor of at least 64 KiB")
+    flop = ctypes.c_double()
+    rc = _lib.mlt_probe_mfma(int(iters), data.data_ptr(), sink.data_ptr(), ctypes.byref(flop),
+                             torch.cuda.current_stream(data.device).cuda_stream)
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_probe_mfma")
+    return flop.value
 
 
 def mlt_query_tiling(op: int, dims, dtype: int):

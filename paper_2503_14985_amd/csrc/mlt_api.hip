@@ -120,6 +120,27 @@ int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const v
   return rc;
 }
 
+int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* stream) {
+  if (iters < 1 || iters > (1 << 20) || !data || !sink || !flop) return MLT_ERR_INVALID_ARG;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  int dev = 0, ncu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return MLT_ERR_DEVICE;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  double f;
+  {
+    TimedRegion t(s);
+    f = run_mfma_probe(iters, ncu, data, (float*)sink, s);
+  }
+  if (f < 0) return MLT_ERR_LAUNCH;
+  *flop = f;
+  g_last_kernel = "mfma_rate_probe";
+  return MLT_OK;
+}
+
 void mlt_set_timing_events(void* start_event, void* stop_event) {
   g_ev_start = (hipEvent_t)start_event;
   g_ev_stop = (hipEvent_t)stop_event;

@@ -57,6 +57,9 @@ struct MhaPlan {
 bool mha_pp_ok(const MhaArgs& a);
 int run_mha_pp(const MhaArgs& a, hipStream_t s);
 
+// probe.hip: launches the register-only MFMA loop, returns the flop it will execute (< 0: launch failed)
+double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, hipStream_t s);
+
 MhaPlan plan_mha(const MhaArgs& a);
 int run_mha(const MhaArgs& a, const MhaPlan& p, hipStream_t s);
 

@@ -56,6 +56,26 @@ def test_gemm_argument_validation_without_device(binding):
     assert g(8, 0, 8, null, 8, null, 16, 0, null, 16, 1, None) == binding.MLT_OK        # N = 0: no-op
 
 
+def test_probe_argument_validation_without_device(binding):
+    lib = binding.raw()
+    p = ctypes.c_void_p(0x1000)
+    flop = ctypes.c_double()
+    f = lib.mlt_probe_mfma
+    assert f(0, p, p, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG          # iters < 1
+    assert f(1 << 21, p, p, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG    # iters too large
+    assert f(16, None, p, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG      # data null
+    assert f(16, p, None, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG      # sink null
+    assert f(16, p, p, None, None) == binding.MLT_ERR_INVALID_ARG                       # flop null
+
+
+def test_skinny_shapes_are_routed_by_the_tiling_query(binding):
+    # M <= 64 with B stored N x K and enough columns: 16-column workgroups, 16x16x32 MFMA
+    t = binding.mlt_query_tiling(0, (16, 4096, 4096, 1), 0)
+    assert list(t[:2]) == [16, 16] and list(t[6:9]) == [16, 16, 32]
+    t = binding.mlt_query_tiling(0, (16, 4096, 4096, 0), 0)      # row-major B: the tile kernels
+    assert list(t[6:9]) == [32, 32, 16]
+
+
 def test_mha_argument_validation_without_device(binding):
     lib = binding.raw()
     p = ctypes.c_void_p(0x1000)
