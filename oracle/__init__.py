@@ -6,6 +6,8 @@ library. The arithmetic lives in ``oracle.c`` (GEMM: Section 2 / Listing 1 of ar
 attention: Section 2.5, Algorithm 1); this file only compiles it with gcc and marshals numpy
 arrays of raw 16-bit patterns (``uint16``) through ctypes.
 
+Paged attention for decoding (Section 3.2) is ``paged_attn_decode``.
+
 dtype codes: 0 = bf16, 1 = fp16.
 """
 from __future__ import annotations
@@ -56,6 +58,9 @@ def _bind(path: str):
     lib.oracle_mha_fwd_rows.restype = i32
     lib.oracle_mha_fwd_rows.argtypes = [i64, i64, i64, i64, i64, p, p, p, i64, p, p, p, p, p,
                                         dbl, i32, i32, i32]
+    lib.oracle_paged_attn_decode.restype = i32
+    lib.oracle_paged_attn_decode.argtypes = [i64, i64, i64, i64, i64, i64, p, p, p, p, p, p, p,
+                                             dbl, i32, i32]
     return lib
 
 
@@ -193,4 +198,30 @@ def mha_fwd_rows(Q, K, V, bs, hs, qs, scale: float, causal: bool, dtype: int,
                                      float(scale), int(causal), dtype, nthreads)
     if rc != 0:
         raise RuntimeError("oracle_mha_fwd_rows failed: %d" % rc)
+    return (O, W) if want_weights else O
+
+
+def paged_attn_decode(Q, Kc, Vc, block_table, seq_lens, scale: float, dtype: int,
+                      want_weights: bool = False, nthreads: int = 0):
+    """O_ref float64 [B, H, D] of one query per (sequence, head) over a paged cache.
+
+    Q [B,H,D] uint16; Kc, Vc [num_blocks, H, block_size, D] uint16; block_table [B, max_blocks]
+    int32; seq_lens [B] int32. With want_weights also the softmax weights
+    [B, H, max_blocks*block_size] (zeros beyond seq_len)."""
+    Q, Kc, Vc = (np.ascontiguousarray(_u16(x)) for x in (Q, Kc, Vc))
+    B, H, D = Q.shape
+    nb, Hc, bs, Dc = Kc.shape
+    assert (Hc, Dc) == (H, D) and Vc.shape == Kc.shape
+    block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    assert block_table.shape[0] == B and seq_lens.shape == (B,)
+    mb = block_table.shape[1]
+    O = np.empty((B, H, D), dtype=np.float64)
+    W = np.empty((B, H, mb * bs), dtype=np.float64) if want_weights else None
+    rc = _load().oracle_paged_attn_decode(B, H, D, bs, mb, nb, _ptr(Q), _ptr(Kc), _ptr(Vc),
+                                          _ptr(block_table), _ptr(seq_lens), _ptr(O),
+                                          _ptr(W) if want_weights else None, float(scale), dtype,
+                                          nthreads)
+    if rc != 0:
+        raise RuntimeError("oracle_paged_attn_decode failed: %d" % rc)
     return (O, W) if want_weights else O

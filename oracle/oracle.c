@@ -2,6 +2,8 @@
  * CPU oracle for the two dense tile kernels of arXiv 2503.14985 ("ML-Triton"):
  *   - GEMM, Section 2 (the C = A*B example, 16-bit inputs with 32-bit accumulate in Listing 1)
  *   - attention forward, Section 2.5, Algorithm 1 (FlashAttention-2 forward)
+ *   - paged attention for decoding, Section 3.2 (one query per sequence, keys and values in
+ *     fixed-size blocks of a cache that a per-sequence block table maps to logical positions)
  *
  * THIS IS TEST INFRASTRUCTURE, not a product path. Only the tests, the smoke check and the
  * bench's cpu_baseline leg may call it. It shares no code with the GPU library.
@@ -266,6 +268,87 @@ int oracle_mha_fwd_rows(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D,
               W ? W + r * Sk : (double*)0, scratch);
     }
     __builtin_free(scratch);
+  }
+  return fail ? -2 : 0;
+}
+
+/* ------------------------------------------------------------------ paged attention, decoding */
+
+/*
+ * Section 3.2 of the paper: attention of ONE query per (sequence b, head h) over that sequence's
+ * cached keys and values, o = sum_j softmax_j(scale * q.k_j) v_j, j = 0 .. seq_len[b]-1. The
+ * paper fixes no storage layout; the one used here (and by the GPU library) is
+ *   Q, O          [B, H, D]
+ *   Kc, Vc        [num_blocks, H, block_size, D]   (the cache: physical blocks)
+ *   block_table   [B, max_blocks] int32: physical block of logical block i of sequence b
+ *   seq_lens      [B] int32, 1 <= seq_len[b] <= max_blocks * block_size
+ * Logical key position p of sequence b is slot p % block_size of physical block
+ * block_table[b][p / block_size]. Table entries and cache slots beyond seq_len are never read.
+ * The definition is written out directly: gather, scores, maximum, exponentials, weighted sum,
+ * all in double; the split over wavefronts and the cross-wavefront reduction that the paper
+ * describes are the GPU method, not part of the definition.
+ * Returns 0, -1 for bad arguments (including a table entry outside [0, num_blocks)), -2 when out
+ * of memory. W (may be NULL) is [B, H, max_blocks * block_size] and receives the weights (zero
+ * beyond seq_len).
+ */
+int oracle_paged_attn_decode(int64_t B, int64_t H, int64_t D, int64_t block_size,
+                             int64_t max_blocks, int64_t num_blocks, const uint16_t* Q,
+                             const uint16_t* Kc, const uint16_t* Vc, const int32_t* block_table,
+                             const int32_t* seq_lens, double* O_ref, double* W, double scale,
+                             int dtype, int nthreads) {
+  if (B < 0 || H < 0 || D <= 0 || block_size <= 0 || max_blocks <= 0 || num_blocks <= 0 ||
+      (dtype != 0 && dtype != 1))
+    return -1;
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t len = seq_lens[b];
+    if (len < 1 || len > max_blocks * block_size) return -1;
+    for (int64_t i = 0; i * block_size < len; ++i) {
+      int64_t pb = block_table[b * max_blocks + i];
+      if (pb < 0 || pb >= num_blocks) return -1;
+    }
+  }
+  set_threads(nthreads);
+  int fail = 0;
+  const int64_t cap = max_blocks * block_size;
+#pragma omp parallel
+  {
+    double* s = (double*)__builtin_malloc(sizeof(double) * (size_t)cap);
+    if (!s) {
+#pragma omp atomic write
+      fail = 1;
+    }
+#pragma omp for schedule(dynamic, 4)
+    for (int64_t r = 0; r < B * H; ++r) {
+      if (!s) continue;
+      const int64_t b = r / H, h = r % H, len = seq_lens[b];
+      const uint16_t* q = Q + r * D;
+      double m = -INFINITY;
+      for (int64_t p = 0; p < len; ++p) {
+        const int64_t pb = block_table[b * max_blocks + p / block_size];
+        const uint16_t* k = Kc + ((pb * H + h) * block_size + p % block_size) * D;
+        double dot = 0.0;
+        for (int64_t d = 0; d < D; ++d) dot += widen(q[d], dtype) * widen(k[d], dtype);
+        s[p] = scale * dot;
+        if (s[p] > m) m = s[p];
+      }
+      double l = 0.0;
+      for (int64_t p = 0; p < len; ++p) {
+        s[p] = exp(s[p] - m);
+        l += s[p];
+      }
+      double* o = O_ref + r * D;
+      for (int64_t d = 0; d < D; ++d) o[d] = 0.0;
+      for (int64_t p = 0; p < len; ++p) {
+        const int64_t pb = block_table[b * max_blocks + p / block_size];
+        const uint16_t* v = Vc + ((pb * H + h) * block_size + p % block_size) * D;
+        const double wp = s[p] / l;
+        if (W) W[r * cap + p] = wp;
+        for (int64_t d = 0; d < D; ++d) o[d] += wp * widen(v[d], dtype);
+      }
+      if (W)
+        for (int64_t p = len; p < cap; ++p) W[r * cap + p] = 0.0;
+    }
+    __builtin_free(s);
   }
   return fail ? -2 : 0;
 }

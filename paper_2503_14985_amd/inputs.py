@@ -80,3 +80,40 @@ def mha_inputs(B: int, H: int, Sq: int, Sk: int, D: int, dtype: int, seed: int,
     k = to_bits(_draw(rng, (B, H, Sk, D), "normal", 1.0), dtype)
     v = to_bits(_draw(rng, (B, H, Sk, D), "normal", 1.0), dtype)
     return q, k, v
+
+
+def paged_inputs(B: int, H: int, D: int, block_size: int, seq_lens, dtype: int, seed: int,
+                 extra_blocks: int = 3, shuffle: bool = True, poison: bool = False):
+    """A paged KV cache for decoding: Q [B,H,D]; Kc, Vc [num_blocks, H, block_size, D]; block_table
+    [B, max_blocks] int32; seq_lens [B] int32; plus the logical (dense) keys and values as lists of
+    [H, len_b, D] arrays, from which the cache was filled. Values i.i.d. N(0,1). Physical blocks
+    are handed out in a random order when `shuffle`; `extra_blocks` blocks stay unused. With
+    `poison`, everything a correct reader never touches (slots past seq_len, unused blocks, table
+    entries past the last block) holds NaN patterns / an out-of-range block number."""
+    rng = np.random.default_rng(seed)
+    seq_lens = np.asarray(seq_lens, dtype=np.int32)
+    assert seq_lens.shape == (B,) and seq_lens.min() >= 1
+    nblk = (seq_lens.astype(np.int64) + block_size - 1) // block_size
+    max_blocks = int(nblk.max())
+    num_blocks = int(nblk.sum()) + extra_blocks
+    q = to_bits(_draw(rng, (B, H, D), "normal", 1.0), dtype)
+    fill = 0x7FC1 if dtype == BF16 else 0x7E01            # a NaN in either format
+    kc = np.full((num_blocks, H, block_size, D), fill if poison else 0, dtype=np.uint16)
+    vc = np.full((num_blocks, H, block_size, D), fill if poison else 0, dtype=np.uint16)
+    table = np.full((B, max_blocks), num_blocks + 7 if poison else 0, dtype=np.int32)
+    order = rng.permutation(num_blocks) if shuffle else np.arange(num_blocks)
+    nxt = 0
+    k_dense, v_dense = [], []
+    for b in range(B):
+        n = int(seq_lens[b])
+        k = to_bits(_draw(rng, (H, n, D), "normal", 1.0), dtype)
+        v = to_bits(_draw(rng, (H, n, D), "normal", 1.0), dtype)
+        k_dense.append(k)
+        v_dense.append(v)
+        for i in range(int(nblk[b])):
+            pb = int(order[nxt]); nxt += 1
+            table[b, i] = pb
+            lo, hi = i * block_size, min((i + 1) * block_size, n)
+            kc[pb, :, : hi - lo, :] = k[:, lo:hi, :]
+            vc[pb, :, : hi - lo, :] = v[:, lo:hi, :]
+    return q, kc, vc, table, seq_lens, k_dense, v_dense

@@ -27,6 +27,15 @@ MUTATIONS = [
      "o[d] += wj * widen(kbase[j * D + d], dtype);"),
     ("attention: query row ignored", "Q + ((b * H + h) * Sq + i) * D;",
      "Q + ((b * H + h) * Sq) * D;"),
+    ("paged: slot taken from the block number", "+ p % block_size) * D;\n        double dot",
+     "+ p / block_size) * D;\n        double dot"),
+    ("paged: keys past seq_len included", "for (int64_t p = 0; p < len; ++p) {\n        s[p] = exp",
+     "for (int64_t p = 0; p < cap; ++p) {\n        s[p] = exp"),
+    ("paged: table row of sequence 0", "block_table[b * max_blocks + p / block_size];\n        const uint16_t* v",
+     "block_table[p / block_size];\n        const uint16_t* v"),
+    ("paged: head stride dropped for K", "Kc + ((pb * H + h) * block_size", "Kc + ((pb * H) * block_size"),
+    ("paged: scale dropped", "s[p] = scale * dot;", "s[p] = dot;"),
+    ("paged: weights not normalised", "const double wp = s[p] / l;", "const double wp = s[p];"),
     ("gemm: B read transposed", "transB ? B[j * ldb + k] : B[k * ldb + j]",
      "transB ? B[k * ldb + j] : B[j * ldb + k]"),
     ("gemm: last k dropped", "for (int64_t k = 0; k < K; ++k) {\n    double a = widen(A[i",
