@@ -76,6 +76,29 @@ int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const v
                 void* stream);
 
 /*
+ * Paged attention for decoding, Section 3.2 of the paper: ONE query per (sequence b, head h) over
+ * the seq_lens[b] keys and values of that sequence, which live in fixed-size blocks of a cache:
+ *   o = sum_j softmax_j(scale * q . k_j) v_j,   j = 0 .. seq_lens[b] - 1.
+ * The keys are split over the wavefronts of a workgroup and the partial maxima, sums and outputs
+ * are reduced through LDS (the paper's warp-level decomposition, Listing 6); weights are rounded
+ * to `dtype` before they multiply V (Listing 5). The paper fixes no storage layout; this one is
+ *   Q, O          device, contiguous [B, H, D]
+ *   Kc, Vc        device, contiguous [num_blocks, H, block_size, D]: the cache, physical blocks
+ *   block_table   device, int32 [B, max_blocks]: physical block of logical block i of sequence b;
+ *                 logical key p is slot p % block_size of block block_table[b][p / block_size]
+ *   seq_lens      device, int32 [B], 1 <= seq_lens[b] <= max_blocks * block_size
+ * Table entries and cache slots past seq_lens[b] are never read. The library cannot inspect
+ * device data: an entry outside [0, num_blocks) or a length outside its range is CLAMPED into it
+ * (wrong result for that sequence, no out-of-range access).
+ * D must be 64 or 128, block_size a multiple of 16 up to 1024 (else MLT_ERR_UNSUPPORTED); Q, Kc
+ * and Vc 16-byte aligned, scale finite (MLT_ERR_INVALID_ARG). B or H equal to 0 is a no-op.
+ */
+int mlt_paged_attn_decode(int64_t B, int64_t H, int64_t D, int64_t block_size, int64_t max_blocks,
+                          int64_t num_blocks, const void* Q, const void* Kc, const void* Vc,
+                          const int32_t* block_table, const int32_t* seq_lens, void* O,
+                          float scale, int dtype, void* stream);
+
+/*
  * Diagnostic for benchmarks (not part of the paper's method): enqueues one kernel in which every
  * wavefront of the chip issues bf16 32x32x16 MFMAs back to back from registers, `iters` times 32
  * of them, 8 wavefronts per CU. The rate it reaches is the practical MFMA ceiling FOR THE GIVEN

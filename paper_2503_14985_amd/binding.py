@@ -19,7 +19,8 @@ MLT_BF16, MLT_FP16 = 0, 1
 MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE = 0, -1, -2, -3, -4
 
 EXPORTS = ("mlt_gemm", "mlt_mha_fwd", "mlt_set_timing_events", "mlt_last_kernel",
-           "mlt_query_tiling", "mlt_status_string", "mlt_version", "mlt_probe_mfma")
+           "mlt_query_tiling", "mlt_status_string", "mlt_version", "mlt_probe_mfma",
+           "mlt_paged_attn_decode")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -33,6 +34,9 @@ _lib.mlt_gemm.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, 
 _lib.mlt_mha_fwd.restype = _i32
 _lib.mlt_mha_fwd.argtypes = [_i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, ctypes.c_float, _i32,
                              _i32, _p]
+_lib.mlt_paged_attn_decode.restype = _i32
+_lib.mlt_paged_attn_decode.argtypes = [_i64, _i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, _p, _p,
+                                       ctypes.c_float, _i32, _p]
 _lib.mlt_probe_mfma.restype = _i32
 _lib.mlt_probe_mfma.argtypes = [_i32, _p, _p, ctypes.POINTER(ctypes.c_double), _p]
 _lib.mlt_set_timing_events.restype = None
@@ -66,6 +70,33 @@ def mlt_version() -> str:
 
 def mlt_last_kernel() -> str:
     return _lib.mlt_last_kernel().decode()
+
+
+def mlt_paged_attn_decode(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
+                          block_table: torch.Tensor, seq_lens: torch.Tensor, scale: float,
+                          O: torch.Tensor = None) -> torch.Tensor:
+    """Q [B,H,D]; Kc, Vc [num_blocks,H,block_size,D]; block_table int32 [B,max_blocks]; seq_lens
+    int32 [B]; returns O [B,H,D]. All on the GPU, contiguous."""
+    B, H, D = Q.shape
+    nb, Hc, bs, Dc = Kc.shape
+    if (Hc, Dc) != (H, D) or Vc.shape != Kc.shape or Vc.dtype != Q.dtype or Kc.dtype != Q.dtype:
+        raise ValueError("mlt_paged_attn_decode: cache shape/dtype does not match Q")
+    if block_table.dtype != torch.int32 or seq_lens.dtype != torch.int32:
+        raise ValueError("mlt_paged_attn_decode: block_table and seq_lens must be int32")
+    if block_table.shape[0] != B or tuple(seq_lens.shape) != (B,):
+        raise ValueError("mlt_paged_attn_decode: block_table / seq_lens shape")
+    for t in (Q, Kc, Vc, block_table, seq_lens):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("mlt_paged_attn_decode: tensors must be contiguous GPU tensors")
+    if O is None:
+        O = torch.empty_like(Q)
+    rc = _lib.mlt_paged_attn_decode(B, H, D, bs, block_table.shape[1], nb, Q.data_ptr(),
+                                    Kc.data_ptr(), Vc.data_ptr(), block_table.data_ptr(),
+                                    seq_lens.data_ptr(), O.data_ptr(), float(scale),
+                                    _dtype_code(Q), torch.cuda.current_stream(Q.device).cuda_stream)
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_paged_attn_decode")
+    return O
 
 
 def mlt_probe_mfma(iters: int, data: torch.Tensor, sink: torch.Tensor) -> float:

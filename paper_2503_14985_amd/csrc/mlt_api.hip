@@ -120,6 +120,35 @@ int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const v
   return rc;
 }
 
+int mlt_paged_attn_decode(int64_t B, int64_t H, int64_t D, int64_t block_size, int64_t max_blocks,
+                          int64_t num_blocks, const void* Q, const void* Kc, const void* Vc,
+                          const int32_t* block_table, const int32_t* seq_lens, void* O,
+                          float scale, int dtype, void* stream) {
+  if (dtype != MLT_BF16 && dtype != MLT_FP16) return MLT_ERR_INVALID_ARG;
+  if (B < 0 || H < 0 || D <= 0 || block_size <= 0 || max_blocks <= 0 || num_blocks <= 0)
+    return MLT_ERR_INVALID_ARG;
+  if (!(scale == scale) || scale - scale != 0.f) return MLT_ERR_INVALID_ARG;   // NaN or infinite
+  if (D != 64 && D != 128) return MLT_ERR_UNSUPPORTED;
+  if (block_size % 16 || block_size > 1024) return MLT_ERR_UNSUPPORTED;
+  if (B == 0 || H == 0) return MLT_OK;
+  if (!Q || !Kc || !Vc || !block_table || !seq_lens || !O) return MLT_ERR_INVALID_ARG;
+  auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  if (!al16(Q) || !al16(Kc) || !al16(Vc)) return MLT_ERR_INVALID_ARG;
+  if (B * H > INT_MAX || max_blocks * block_size > INT_MAX || num_blocks > INT_MAX)
+    return MLT_ERR_UNSUPPORTED;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  PagedArgs a{B, H, D, block_size, max_blocks, num_blocks, (const uint16_t*)Q, (const uint16_t*)Kc,
+              (const uint16_t*)Vc, block_table, seq_lens, (uint16_t*)O, scale, dtype};
+  hipStream_t s = (hipStream_t)stream;
+  int rc;
+  {
+    TimedRegion t(s);
+    rc = run_paged_decode(a, s);
+  }
+  if (rc == MLT_OK) g_last_kernel = D == 128 ? "paged_decode_d128_w4" : "paged_decode_d64_w4";
+  return rc;
+}
+
 int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* stream) {
   if (iters < 1 || iters > (1 << 20) || !data || !sink || !flop) return MLT_ERR_INVALID_ARG;
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;

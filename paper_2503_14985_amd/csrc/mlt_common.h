@@ -43,6 +43,9 @@ template <> struct Elem<bf16_tag> {
     bf16x2 h = __builtin_convertvector(v, bf16x2);
     return __builtin_bit_cast(uint32_t, h);
   }
+  static __device__ __forceinline__ float to_f32(uint16_t bits) {
+    return __builtin_bit_cast(float, (uint32_t)bits << 16);
+  }
   // acc + lo + hi of a packed pair, exact in fp32 (v_dot2c_f32_bf16 against (1, 1))
   static __device__ __forceinline__ float add_pair(uint32_t packed, float acc) {
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -62,6 +65,9 @@ template <> struct Elem<f16_tag> {
     f32x2 v = {lo, hi};
     f16x2 h = __builtin_convertvector(v, f16x2);
     return __builtin_bit_cast(uint32_t, h);
+  }
+  static __device__ __forceinline__ float to_f32(uint16_t bits) {
+    return (float)__builtin_bit_cast(_Float16, bits);
   }
   // acc + lo + hi of a packed pair (v_dot2c_f32_f16 against (1, 1))
   static __device__ __forceinline__ float add_pair(uint32_t packed, float acc) {

@@ -63,4 +63,14 @@ double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, hip
 MhaPlan plan_mha(const MhaArgs& a);
 int run_mha(const MhaArgs& a, const MhaPlan& p, hipStream_t s);
 
+struct PagedArgs {
+  int64_t B, H, D, block_size, max_blocks, num_blocks;
+  const uint16_t *Q, *Kc, *Vc;
+  const int32_t *block_table, *seq_lens;
+  uint16_t* O;
+  float scale;
+  int dtype;
+};
+int run_paged_decode(const PagedArgs& a, hipStream_t s);   // paged.hip
+
 }  // namespace mlt
