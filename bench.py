@@ -93,6 +93,46 @@ def cpu_baseline(A, B, Q, K, V, scale):
     }
 
 
+PAGED_SHAPE = (64, 32, 4096, 128, 16)   # sequences, heads, keys per sequence, head dim, block size
+
+
+def paged_decode(binding, ev, dev):
+    """The paged-attention decode kernel (paper Section 3.2) on a bf16 cache of B x H x S keys in
+    shuffled 16-key blocks (N(0,1), torch seed 0, generated on the device): HBM-bound, reported in
+    GB/s of algorithmic bytes (K and V cache read once, Q and O) against the 8 TB/s peak."""
+    import torch
+    Bp, Hp, Sp, Dp, bs = PAGED_SHAPE
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    nb = Bp * (Sp // bs)
+    kc = torch.randn((nb, Hp, bs, Dp), generator=g, device=dev, dtype=torch.bfloat16)
+    vc = torch.randn((nb, Hp, bs, Dp), generator=g, device=dev, dtype=torch.bfloat16)
+    q = torch.randn((Bp, Hp, Dp), generator=g, device=dev, dtype=torch.bfloat16)
+    table = torch.randperm(nb, generator=g, device=dev).to(torch.int32).reshape(Bp, -1).contiguous()
+    lens = torch.full((Bp,), Sp, dtype=torch.int32, device=dev)
+    o = torch.empty_like(q)
+    scale = 1.0 / math.sqrt(Dp)
+    for _ in range(3):
+        binding.mlt_paged_attn_decode(q, kc, vc, table, lens, scale, O=o)
+    reps = 10
+    e0, e1 = ev.create(), ev.create()
+    binding.mlt_set_timing_events(e0, None)
+    binding.mlt_paged_attn_decode(q, kc, vc, table, lens, scale, O=o)
+    binding.mlt_set_timing_events(None, None)
+    for _ in range(reps - 2):
+        binding.mlt_paged_attn_decode(q, kc, vc, table, lens, scale, O=o)
+    binding.mlt_set_timing_events(None, e1)
+    binding.mlt_paged_attn_decode(q, kc, vc, table, lens, scale, O=o)
+    binding.mlt_set_timing_events(None, None)
+    torch.cuda.synchronize()
+    ms = ev.elapsed_ms(e0, e1) / reps
+    nbytes = 2.0 * Bp * Hp * Sp * Dp * 2 + 2.0 * Bp * Hp * Dp * 2 + table.numel() * 4
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"kernel": binding.mlt_last_kernel(), "avg_ms": ms, "GB_per_s": gbs,
+            "frac_hbm_peak": gbs / 8000.0, "bytes_per_launch": nbytes,
+            "workload": "B=%d H=%d S=%d D=%d block=%d bf16, shuffled blocks" % PAGED_SHAPE}
+
+
 def mfma_ceiling(binding, ev, A, dev):
     """Rate of a register-only MFMA loop over the whole chip (mlt_probe_mfma) on all-zero operands
     and on the GEMM's own N(0,1) operand values: the second is what the chip's power management
@@ -239,6 +279,7 @@ def main():
     }
     if not args.no_ceiling:
         out["mfma_ceiling"] = mfma_ceiling(binding, ev, A, dev)
+        out["paged_decode"] = paged_decode(binding, ev, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(A_h, B_h, Q_h, K_h, V_h, scale)
     print(json.dumps(out))

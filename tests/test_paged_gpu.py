@@ -119,3 +119,37 @@ def test_argument_errors():
     with pytest.raises(binding.MltError) as e:
         binding.mlt_paged_attn_decode(q, kc, kc, t, l, float("nan"))
     assert e.value.status == binding.MLT_ERR_INVALID_ARG
+
+
+def test_bench_size_sampled_heads():
+    """The bench workload (64 sequences x 32 heads x 4096 keys, shuffled 16-key blocks), generated
+    on the device; the oracle recomputes 12 sampled (sequence, head) outputs from their blocks."""
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    Bp, Hp, Sp, Dp, bs = 64, 32, 4096, 128, 16
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    nb = Bp * (Sp // bs)
+    kc = torch.randn((nb, Hp, bs, Dp), generator=g, device=dev, dtype=torch.bfloat16)
+    vc = torch.randn((nb, Hp, bs, Dp), generator=g, device=dev, dtype=torch.bfloat16)
+    q = torch.randn((Bp, Hp, Dp), generator=g, device=dev, dtype=torch.bfloat16)
+    table = torch.randperm(nb, generator=g, device=dev).to(torch.int32).reshape(Bp, -1).contiguous()
+    lens = torch.full((Bp,), Sp, dtype=torch.int32, device=dev)
+    lens[3] = 4001                                          # one ragged sequence among the samples
+    scale = 1.0 / math.sqrt(Dp)
+    O = binding.mlt_paged_attn_decode(q, kc, vc, table, lens, scale)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    picks = [(3, 0), (0, 0), (Bp - 1, Hp - 1)] + [(int(rng.integers(Bp)), int(rng.integers(Hp))) for _ in range(9)]
+    worst = 0.0
+    for b, h in picks:
+        blocks = table[b].long()
+        kb = inputs.torch_to_bits(kc[blocks, h].contiguous().cpu())[:, None]      # [nblk, 1, bs, D]
+        vb = inputs.torch_to_bits(vc[blocks, h].contiguous().cpu())[:, None]
+        qb = inputs.torch_to_bits(q[b, h].contiguous().cpu())[None, None]         # [1, 1, D]
+        t = np.arange(blocks.numel(), dtype=np.int32)[None]
+        ref = oracle.paged_attn_decode(qb, kb, vb, t, np.array([int(lens[b])], np.int32), scale, BF16)
+        err = np.abs(O[b, h].double().cpu().numpy() - ref[0, 0]).max()
+        worst = max(worst, float(err))
+    print("   sampled max err %.3g" % worst, flush=True)
+    assert worst <= TOL[BF16]
