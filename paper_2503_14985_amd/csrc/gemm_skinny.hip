@@ -2,14 +2,14 @@
 // (arXiv 2503.14985): memory-bound GEMMs with a small m), B given as the N x K row-major array
 // (k contiguous). The whole cost is reading B once from HBM, so the kernel is built around that
 // stream and nothing is staged in LDS:
-//   * a workgroup owns 16 columns of C (16 rows of the stored B) and all of K; its 8 wavefronts
+//   * a workgroup owns 16, 32 or 64 columns of C (rows of the stored B; more when N is large, so
+//     that an A fragment fetched from L2 serves more columns) and all of K; its 8 wavefronts
 //     take the 32-wide K chunks round-robin, so at any moment the workgroup reads 512 contiguous
 //     bytes of each of its 16 B rows;
 //   * a lane loads 16 bytes (8 consecutive k) of one B row straight into the register that the
 //     16x16x32 MFMA wants as its B operand (lane l: column l % 16, k slots 8*(l/16)..+7), and the
 //     matching 16 bytes of one A row as the A operand; A (M x K, at most 64 rows) stays in L2;
-//   * up to 16 chunks per wavefront are in flight before the first MFMA, which with one
-//     workgroup per CU puts the whole of a 4096 x 4096 B (32 MB) in flight at once;
+//   * 16 KB of B per wavefront are in flight before the first MFMA of a batch;
 //   * the 8 partial 16 x 16 fp32 tiles are added through LDS and rounded to 16 bit once.
 // Requirements (host): transB, M <= 64, K % 8 == 0, lda % 8 == 0, ldb % 8 == 0, A and B 16-byte
 // aligned. N and K need not be multiples of the tile.
@@ -25,18 +25,23 @@ constexpr int SK_NT = SK_NW * 64;
 constexpr int SK_U = 16;            // chunks in flight per wavefront
 constexpr int SK_MAXMT = 4;         // 16-row tiles of A (M <= 64)
 
-template <typename Tag, int MT>
+template <typename Tag, int MT, int NT>
 __global__ __launch_bounds__(SK_NT) void gemm_skinny_nt_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc) {
   typedef typename Elem<Tag>::vec8 V8;
-  __shared__ float red[SK_NW][MT][256];
+  constexpr int U = SK_U / NT;               // chunks per batch: 16 KB of B in flight per wavefront
+  __shared__ float red[SK_NW][256];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r16 = lane & 15, q = lane >> 4;
-  const int n0 = blockIdx.x * 16;
-  const int nrow = n0 + r16 < N ? n0 + r16 : N - 1;       // clamped: extra columns are never stored
-  const uint16_t* bp = B + (int64_t)nrow * ldb;
+  const int n0 = blockIdx.x * (16 * NT);
+  const uint16_t* bp[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int nrow = n0 + nt * 16 + r16 < N ? n0 + nt * 16 + r16 : N - 1;   // clamped: never stored
+    bp[nt] = B + (int64_t)nrow * ldb;
+  }
   const uint16_t* ap[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -44,77 +49,97 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_nt_kernel(
     ap[mt] = A + (int64_t)arow * lda;
   }
 
-  f32x4 acc[MT];
+  f32x4 acc[MT][NT];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int KC = (K + 31) / 32;                            // 32-wide chunks; K % 8 == 0
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  for (int c0 = wave; c0 < KC; c0 += SK_NW * SK_U) {
+  for (int c0 = wave; c0 < KC; c0 += SK_NW * U) {
     // k of this lane's 8 values in chunk u of the batch; past K (last batch only) the loads
     // re-read k = 0 and the B values are zeroed after they have arrived
-    const bool whole = (c0 + (SK_U - 1) * SK_NW) * 32 + 32 <= K;   // wavefront-uniform
-    u32x4 bfrag[SK_U];
+    const bool whole = (c0 + (U - 1) * SK_NW) * 32 + 32 <= K;   // wavefront-uniform
+    u32x4 bfrag[U][NT];
 #pragma unroll
-    for (int u = 0; u < SK_U; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int k = (c0 + u * SK_NW) * 32 + 8 * q;
-      bfrag[u] = *reinterpret_cast<const u32x4_mem*>(bp + ((whole || k < K) ? k : 0));
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        bfrag[u][nt] = *reinterpret_cast<const u32x4_mem*>(bp[nt] + ((whole || k < K) ? k : 0));
     }
     __builtin_amdgcn_sched_barrier(0);                     // all B loads of the batch go out first
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      u32x4 afrag[SK_U];
+      u32x4 afrag[U];
 #pragma unroll
-      for (int u = 0; u < SK_U; ++u) {
+      for (int u = 0; u < U; ++u) {
         const int k = (c0 + u * SK_NW) * 32 + 8 * q;
         afrag[u] = *reinterpret_cast<const u32x4_mem*>(ap[mt] + ((whole || k < K) ? k : 0));
       }
       __builtin_amdgcn_sched_barrier(0);
       if (mt == 0 && !whole) {
 #pragma unroll
-        for (int u = 0; u < SK_U; ++u)
-          if ((c0 + u * SK_NW) * 32 + 8 * q >= K) bfrag[u] = zero4;
+        for (int u = 0; u < U; ++u)
+          if ((c0 + u * SK_NW) * 32 + 8 * q >= K) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) bfrag[u][nt] = zero4;
+          }
       }
 #pragma unroll
-      for (int u = 0; u < SK_U; ++u)
-        acc[mt] = mfma16(__builtin_bit_cast(V8, afrag[u]), __builtin_bit_cast(V8, bfrag[u]), acc[mt]);
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          acc[mt][nt] = mfma16(__builtin_bit_cast(V8, afrag[u]), __builtin_bit_cast(V8, bfrag[u][nt]),
+                               acc[mt][nt]);
     }
   }
 
-  // lane owns C[4*q + r][r16] of each 16-row tile in acc[mt][r]
+  // one 16 x 16 tile at a time through LDS: lane owns C[4*q + r][r16] in acc[..][r]
+  const int row = (tid & 255) >> 4, col = tid & 15;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[wave][mt][(4 * q + r) * 16 + r16] = acc[mt][r];
-  __syncthreads();
-  if (tid < 256) {
-    const int row = tid >> 4, col = tid & 15;
+    for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      float s = 0.f;
+      for (int r = 0; r < 4; ++r) red[wave][(4 * q + r) * 16 + r16] = acc[mt][nt][r];
+      __syncthreads();
+      if (tid < 256) {
+        float s = 0.f;
 #pragma unroll
-      for (int w = 0; w < SK_NW; ++w) s += red[w][mt][tid];
-      const int gr = mt * 16 + row, gc = n0 + col;
-      if (gr < M && gc < N) C[(int64_t)gr * ldc + gc] = Elem<Tag>::from_f32(s);
+        for (int w = 0; w < SK_NW; ++w) s += red[w][tid];
+        const int gr = mt * 16 + row, gc = n0 + nt * 16 + col;
+        if (gr < M && gc < N) C[(int64_t)gr * ldc + gc] = Elem<Tag>::from_f32(s);
+      }
+      __syncthreads();
     }
-  }
 }
 
-template <typename Tag, int MT>
+template <typename Tag, int MT, int NT>
 int launch_skinny(const GemmArgs& g, hipStream_t s) {
-  const unsigned nwg = (unsigned)((g.N + 15) / 16);
-  hipLaunchKernelGGL((gemm_skinny_nt_kernel<Tag, MT>), dim3(nwg), dim3(SK_NT), 0, s, (int)g.M,
+  const unsigned nwg = (unsigned)((g.N + 16 * NT - 1) / (16 * NT));
+  hipLaunchKernelGGL((gemm_skinny_nt_kernel<Tag, MT, NT>), dim3(nwg), dim3(SK_NT), 0, s, (int)g.M,
                      (int)g.N, (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
+}
+
+// Columns per workgroup: more columns reuse each A fragment more often (A comes from L2 once per
+// workgroup), fewer keep the chip full; at least ~2 workgroups per CU are wanted.
+template <typename Tag, int MT>
+int run_skinny_mt(const GemmArgs& g, hipStream_t s) {
+  if (g.N >= 64 * 512) return launch_skinny<Tag, MT, 4>(g, s);
+  if (g.N >= 32 * 512) return launch_skinny<Tag, MT, 2>(g, s);
+  return launch_skinny<Tag, MT, 1>(g, s);
 }
 
 template <typename Tag>
 int run_skinny_t(const GemmArgs& g, hipStream_t s) {
   switch ((g.M + 15) / 16) {
-    case 1: return launch_skinny<Tag, 1>(g, s);
-    case 2: return launch_skinny<Tag, 2>(g, s);
-    case 3: return launch_skinny<Tag, 3>(g, s);
-    case 4: return launch_skinny<Tag, 4>(g, s);
+    case 1: return run_skinny_mt<Tag, 1>(g, s);
+    case 2: return run_skinny_mt<Tag, 2>(g, s);
+    case 3: return run_skinny_mt<Tag, 3>(g, s);
+    case 4: return run_skinny_mt<Tag, 4>(g, s);
   }
   return MLT_ERR_UNSUPPORTED;
 }

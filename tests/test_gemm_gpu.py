@@ -63,7 +63,8 @@ def test_two_group_kernel(shape, transB, dtype):
 
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("shape", [(16, 1024, 4096), (1, 1040, 512), (7, 1500, 264), (33, 2048, 8200),
-                                   (64, 1024, 1000), (48, 1031, 4096 + 32)])
+                                   (64, 1024, 1000), (48, 1031, 4096 + 32),
+                                   (16, 16400, 520), (40, 32 * 1024 + 8, 264)])   # 32 / 64 columns per workgroup
 def test_skinny_kernel(shape, dtype):
     # M <= 64 with B stored N x K: one to four 16-row tiles, ragged N, K with and without a partial
     # last batch (K % 4096 != 0) and a partial last chunk (K % 32 != 0)
