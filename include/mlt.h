@@ -57,6 +57,16 @@ int mlt_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const 
              int64_t ldb, int transB, void* C, int64_t ldc, int dtype, void* stream);
 
 /*
+ * The paper's own form of the GEMM (Section 2, Listing 1): C += A * B with C in fp32, i.e. the
+ * fp32 accumulator is added to what C already holds and nothing is rounded to 16 bit.
+ * A, B, transB, dtype as for mlt_gemm; C is device, M x N row-major fp32, row stride ldc >= N
+ * (in fp32 elements), 4-byte aligned, read and written. M, N or K equal to 0 is a no-op. The
+ * read-modify-write of C is not atomic: do not run two calls on the same C concurrently.
+ */
+int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                 int64_t ldb, int transB, float* C, int64_t ldc, int dtype, void* stream);
+
+/*
  * Attention forward, Section 2.5 / Algorithm 1 of the paper, per batch b and head h:
  *   O = softmax(scale * Q K^T  [+ causal mask]) V
  * computed tile by tile with the online-softmax recurrence (running row maximum m and row sum

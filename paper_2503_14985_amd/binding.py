@@ -20,7 +20,7 @@ MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE
 
 EXPORTS = ("mlt_gemm", "mlt_mha_fwd", "mlt_set_timing_events", "mlt_last_kernel",
            "mlt_query_tiling", "mlt_status_string", "mlt_version", "mlt_probe_mfma",
-           "mlt_paged_attn_decode")
+           "mlt_paged_attn_decode", "mlt_gemm_acc")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -31,6 +31,8 @@ _lib = ctypes.CDLL(LIB_PATH)
 _i64, _p, _i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
 _lib.mlt_gemm.restype = _i32
 _lib.mlt_gemm.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _p]
+_lib.mlt_gemm_acc.restype = _i32
+_lib.mlt_gemm_acc.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _p]
 _lib.mlt_mha_fwd.restype = _i32
 _lib.mlt_mha_fwd.argtypes = [_i64, _i64, _i64, _i64, _i64, _p, _p, _p, _p, ctypes.c_float, _i32,
                              _i32, _p]
@@ -95,7 +97,7 @@ def mlt_paged_attn_decode(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
                                     seq_lens.data_ptr(), O.data_ptr(), float(scale),
                                     _dtype_code(Q), torch.cuda.current_stream(Q.device).cuda_stream)
     if rc != MLT_OK:
-        raise MltError(rc, "mlt_paged_attn_decode")
+        raise MltError(rc, "mlt_paged_attn_decode", "mlt_gemm_acc")
     return O
 
 
@@ -172,6 +174,29 @@ def mlt_gemm(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor | None = None, tr
                            C.data_ptr(), ldc, dt, _stream(stream))
     if rc != MLT_OK:
         raise MltError(rc, "mlt_gemm")
+    return C
+
+
+def mlt_gemm_acc(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor, transB: bool = False,
+                 stream=None) -> torch.Tensor:
+    """C += A @ B (or A @ B.T) with C an fp32 [M, N] tensor that is read and written."""
+    if not (A.is_cuda and B.is_cuda and C.is_cuda):
+        raise ValueError("mlt_gemm_acc needs GPU tensors")
+    dt = _dtype_code(A)
+    if B.dtype != A.dtype:
+        raise TypeError("A and B must share a dtype")
+    M, K = A.shape
+    N, Kb = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
+    if K != Kb:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, Kb))
+    if C.dtype != torch.float32 or tuple(C.shape) != (M, N):
+        raise ValueError("C must be an fp32 [M, N] tensor")
+    lda, ldb, ldc = _rows_contiguous(A, "A"), _rows_contiguous(B, "B"), _rows_contiguous(C, "C")
+    with torch.cuda.device(A.device):
+        rc = _lib.mlt_gemm_acc(M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, int(transB),
+                               C.data_ptr(), ldc, dt, _stream(stream))
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_gemm_acc")
     return C
 
 

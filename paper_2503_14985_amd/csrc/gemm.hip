@@ -77,7 +77,7 @@ template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
-    int nbn) {
+    int nbn, int acc32) {
   typedef GemmTile<Tag, BM, BN, BK, WM, WN, TRANSB> Cfg;
   typedef typename Elem<Tag>::vec8 V8;
   extern __shared__ __align__(16) char smem[];
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (row < M && col < N) C[(int64_t)row * ldc + col] = Elem<Tag>::from_f32(acc[i][j][r]);
+        if (row < M && col < N) store_c<Tag>(C, (int64_t)row * ldc + col, acc[i][j][r], acc32);
       }
     }
 }
@@ -304,7 +304,7 @@ template <typename Tag>
 __global__ __launch_bounds__(256) void gemm_general_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, int transB, uint16_t* __restrict__ C,
-    int64_t ldc) {
+    int64_t ldc, int acc32) {
   typedef typename Elem<Tag>::vec8 V8;
   constexpr int BM = 64, BN = 64, BK = 32, LDS_S = BK + 8;
   __shared__ __align__(16) uint16_t As[BM * LDS_S];
@@ -348,11 +348,11 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int row = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    if (row < M && col < N) C[(int64_t)row * ldc + col] = Elem<Tag>::from_f32(acc[r]);
+    if (row < M && col < N) store_c<Tag>(C, (int64_t)row * ldc + col, acc[r], acc32);
   }
 }
 
-// K == 0: the empty sum.
+// K == 0: the empty sum (only launched when C is overwritten; C += 0 is a no-op).
 __global__ void gemm_zero_kernel(int M, int N, uint16_t* __restrict__ C, int64_t ldc) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e < (int64_t)M * N) C[(e / N) * ldc + (e % N)] = 0;
@@ -378,7 +378,7 @@ static int launch_tile(const GemmArgs& g, hipStream_t s) {
   }
   const int nbm = (int)((g.M + BM - 1) / BM), nbn = (int)((g.N + BN - 1) / BN);
   hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(Cfg::NT), Cfg::SMEM, s, (int)g.M, (int)g.N,
-                     (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn);
+                     (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.acc32);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
@@ -386,7 +386,7 @@ template <typename Tag>
 static int launch_general(const GemmArgs& g, hipStream_t s) {
   dim3 grid((unsigned)((g.N + 63) / 64), (unsigned)((g.M + 63) / 64));
   hipLaunchKernelGGL(gemm_general_kernel<Tag>, grid, dim3(256), 0, s, (int)g.M, (int)g.N, (int)g.K,
-                     g.A, g.lda, g.B, g.ldb, g.transB, g.C, g.ldc);
+                     g.A, g.lda, g.B, g.ldb, g.transB, g.C, g.ldc, g.acc32);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
@@ -444,6 +444,7 @@ template <typename Tag>
 static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
   switch (p.variant) {
     case GEMM_ZERO: {
+      if (g.acc32) return MLT_OK;
       const int64_t n = g.M * g.N;
       hipLaunchKernelGGL(gemm_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                          (int)g.M, (int)g.N, g.C, g.ldc);

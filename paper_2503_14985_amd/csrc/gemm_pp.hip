@@ -88,7 +88,7 @@ template <typename Tag, bool TRANSB>
 __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
-    int nbn) {
+    int nbn, int acc32) {
   typedef typename Elem<Tag>::vec8 V8;
   extern __shared__ __align__(16) char smem[];
 
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   }
   if (grp == 0) __builtin_amdgcn_s_barrier();
 
-  // ---- epilogue: fp32 -> 16-bit (RNE), guarded element stores
+  // ---- epilogue: fp32 -> 16-bit (RNE) and store, or add to the fp32 C; guarded per element
   const int row_base = m0 + wm * 128 + 4 * h;
   const int col_base = n0 + wn * 64 + lq;
 #pragma unroll
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (row < M && col < N) C[(int64_t)row * ldc + col] = Elem<Tag>::from_f32(acc[i][j][r]);
+        if (row < M && col < N) store_c<Tag>(C, (int64_t)row * ldc + col, acc[i][j][r], acc32);
       }
     }
 }
@@ -300,7 +300,7 @@ static int launch_pp(const GemmArgs& g, hipStream_t s) {
   }
   const int nbm = (int)((g.M + PP_BM - 1) / PP_BM), nbn = (int)((g.N + PP_BN - 1) / PP_BN);
   hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(PP_NT), PP_SMEM, s, (int)g.M, (int)g.N, (int)g.K,
-                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn);
+                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.acc32);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 

@@ -89,7 +89,26 @@ int mlt_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const 
   if (M == 0 || N == 0) return MLT_OK;
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
   GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
-             (uint16_t*)C, ldc, dtype, forced_gemm_variant()};
+             (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 0};
+  GemmPlan p = plan_gemm(g);
+  hipStream_t s = (hipStream_t)stream;
+  {
+    TimedRegion t(s);
+    rc = run_gemm(g, p, s);
+  }
+  if (rc == MLT_OK) g_last_kernel = p.name;
+  return rc;
+}
+
+int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                 int64_t ldb, int transB, float* C, int64_t ldc, int dtype, void* stream) {
+  int rc = check_gemm(M, N, K, A, lda, B, ldb, transB, C, ldc, dtype);
+  if (rc != MLT_OK) return rc;
+  if (M == 0 || N == 0 || K == 0) return MLT_OK;          // C += (empty sum)
+  if (reinterpret_cast<uintptr_t>(C) & 3) return MLT_ERR_INVALID_ARG;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
+             (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 1};
   GemmPlan p = plan_gemm(g);
   hipStream_t s = (hipStream_t)stream;
   {
@@ -184,7 +203,7 @@ int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]) 
     if (dims[0] < 0 || dims[1] < 0 || dims[2] < 0) return MLT_ERR_INVALID_ARG;
     // Alignment is unknown here: assume aligned pointers and tight leading dimensions.
     GemmArgs g{dims[0], dims[1], dims[2], nullptr, dims[2], nullptr, dims[3] ? dims[2] : dims[1],
-               dims[3] ? 1 : 0, nullptr, dims[1], dtype, forced_gemm_variant()};
+               dims[3] ? 1 : 0, nullptr, dims[1], dtype, forced_gemm_variant(), 0};
     GemmPlan p = plan_gemm(g);
     if (p.variant == GEMM_ZERO) { for (int i = 0; i < 10; ++i) out[i] = 0; return MLT_OK; }
     out[0] = p.bm; out[1] = p.bn; out[2] = p.wm; out[3] = p.wn;

@@ -77,6 +77,15 @@ template <> struct Elem<f16_tag> {
   }
 };
 
+// One element of the GEMM result: rounded to the 16-bit type and stored (the default), or added
+// to the fp32 value already there (the paper's C += A*B with an fp32 C, Section 2 / Listing 1;
+// `idx` then counts fp32 elements).
+template <typename Tag>
+__device__ __forceinline__ void store_c(uint16_t* C, int64_t idx, float v, int acc32) {
+  if (acc32) reinterpret_cast<float*>(C)[idx] += v;
+  else C[idx] = Elem<Tag>::from_f32(v);
+}
+
 // D(32x32) += A(32x16) * B(16x32). Lane l supplies A[l%32][8*(l/32) .. +7] and
 // B[8*(l/32) .. +7][l%32]; it owns D[8*(r/4) + 4*(l/32) + r%4][l%32] in register r (0..15).
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {

@@ -24,6 +24,7 @@ struct GemmArgs {
   uint16_t* C; int64_t ldc;
   int dtype;
   int forced;  // GemmVariant or GEMM_AUTO
+  int acc32;   // 0: C is 16-bit and overwritten; 1: C is fp32 and accumulated into (C += A*B)
 };
 
 struct GemmPlan {

@@ -142,3 +142,51 @@ def test_config2_square_sweep(dtype, n):
 def test_config3_llm_shapes_transB(shape):
     M, N, K = shape
     _go(M, N, K, BF16, True, std=0.02, seed=0)
+
+
+@pytest.mark.parametrize("variant", [None, "256pp", "128", "general"])
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+def test_accumulate_into_fp32_c(variant, transB, dtype):
+    """The paper's form of the GEMM (Listing 1): C(fp32) += A*B. Expected value: the fp32 C widened
+    to double plus the oracle's fp64 product; error budget: fp32 accumulation over K terms plus the
+    final fp32 addition (no 16-bit rounding anywhere)."""
+    import oracle
+    from paper_2503_14985_amd import binding
+    M, N, K = 520, 776, 320
+    A, B = inputs.gemm_inputs(M, N, K, dtype, 8, transB=transB)
+    rng = np.random.default_rng(8)
+    C0 = rng.standard_normal((M, N)).astype(np.float32) * 10.0
+    dev = torch.device("cuda:0")
+    Ct = torch.from_numpy(C0.copy()).to(dev)
+    if variant:
+        os.environ["MLT_GEMM_VARIANT"] = variant
+    At, Bt = inputs.bits_to_torch(A, dtype, dev), inputs.bits_to_torch(B, dtype, dev)
+    binding.mlt_gemm_acc(At, Bt, Ct, transB=transB)
+    binding.mlt_gemm_acc(At, Bt, Ct, transB=transB)          # twice: C0 + 2 A*B
+    torch.cuda.synchronize()
+    print("   kernel=%s" % binding.mlt_last_kernel(), flush=True)
+    Cref, T = oracle.gemm(A, B, dtype, transB=transB)
+    want = C0.astype(np.float64) + 2.0 * Cref
+    err = np.abs(Ct.double().cpu().numpy() - want)
+    bound = 2.0 * (K * 2.0 ** -24) * T + 2.0 ** -22 * (np.abs(C0) + 2.0 * T) + 1e-6
+    assert np.all(err <= bound), "worst err/bound %.3f" % float(np.max(err / bound))
+
+
+def test_accumulate_edge_cases():
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    C = torch.full((5, 7), 3.25, dtype=torch.float32, device=dev)
+    binding.mlt_gemm_acc(torch.empty((5, 0), dtype=torch.bfloat16, device=dev),
+                         torch.empty((0, 7), dtype=torch.bfloat16, device=dev), C)
+    torch.cuda.synchronize()
+    assert torch.all(C == 3.25)                                # K = 0: C += 0
+    # a skinny shape must not take the 16-bit-output skinny kernel
+    A = torch.ones((4, 64), dtype=torch.bfloat16, device=dev)
+    B = torch.ones((2048, 64), dtype=torch.bfloat16, device=dev)
+    C = torch.zeros((4, 2048), dtype=torch.float32, device=dev)
+    binding.mlt_gemm_acc(A, B, C, transB=True)
+    torch.cuda.synchronize()
+    assert "skinny" not in binding.mlt_last_kernel() and torch.all(C == 64.0)
+    with pytest.raises(ValueError):
+        binding.mlt_gemm_acc(A, B, torch.zeros((4, 2048), dtype=torch.bfloat16, device=dev), transB=True)
