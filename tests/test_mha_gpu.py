@@ -110,3 +110,12 @@ def test_config4_noncausal_full_size(dtype):
 @pytest.mark.parametrize("S", [1024, 4096, 16384])
 def test_config5_causal(S, D):
     _go(1, 32, S, S, D, BF16, True, seed=0, n_rows=512 if S <= 4096 else 160)
+
+
+@pytest.mark.parametrize("H,D", [(32, 64), (16, 128)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_paper_sweep_shape_fp16(H, D, causal):
+    """One point of the paper's FlashAttention-2 sweep (Section 4.2: 32k tokens in total, hidden 2048
+    as 32 heads x 64 or 16 heads x 128, fp16), here sequence 2048 x batch 16; sampled rows."""
+    st = _go(16, H, 2048, 2048, D, FP16, causal, seed=0, n_rows=256)
+    assert st["rel_rms"] < 2e-3
