@@ -28,8 +28,8 @@ MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16: 256 CUs x 2.4 GHz x
 # runs summarised under profiles/ (counter x the factor a plain copy of known size gives).
 # Keyed by kernel variant; None when a variant has not been measured.
 MEASURED_TRAFFIC_BYTES = {
-    "mha_fwd_d128_256x64_pp": int((2.0 * 196673.2 + 131072.0) * 1024),
-    "gemm_nn_256x256x64_w2x4_pp": int((2.0 * 797189.5 + 140563.6) * 1024),
+    "mha_fwd_d128_256x64_pp": int((2.0 * 196673 + 131072) * 1024),
+    "gemm_nn_256x256x64_w2x4_pp": int((2.0 * 796299 + 141958) * 1024),
 }
 GEMM_MNK = (8192, 8192, 8192)
 MHA_SHAPE = (4, 32, 4096, 4096, 128)   # B, H, Sq, Sk, D
@@ -169,8 +169,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle timing (used when profiling)")
-    ap.add_argument("--only", choices=["gemm", "mha"], default=None,
-                    help="run only one of the two kernels per step (for counter runs of one kernel)")
+    ap.add_argument("--only", choices=["gemm", "mha", "paged"], default=None,
+                    help="run only one kernel (for counter runs of that kernel): one of the two of "
+                         "the step, or the paged-attention decode kernel")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the measurement of the power-limited MFMA ceiling")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -188,6 +189,21 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    def copy_calibration():
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 256 MiB, writes 256 MiB per launch
+        torch.cuda.synchronize()
+
+    if args.only == "paged":
+        r = paged_decode(binding, HipEvents(), dev)
+        if args.copy_calibration:
+            copy_calibration()
+        print("paged: %s avg %.4f ms, %.1f GB/s" % (r["kernel"], r["avg_ms"], r["GB_per_s"]))
+        return
+
     M, N, Kd = GEMM_MNK
     Bq, H, Sq, Sk, D = MHA_SHAPE
     scale = 1.0 / math.sqrt(D)
@@ -228,11 +244,7 @@ def main():
     elapsed = time.perf_counter() - t0
 
     if args.copy_calibration:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)          # reads 256 MiB, writes 256 MiB per launch
-        torch.cuda.synchronize()
+        copy_calibration()
 
     if args.only is not None:
         # counter / trace runs of a single kernel: no JSON line, just the kernel's own time

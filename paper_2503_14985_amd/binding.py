@@ -97,7 +97,7 @@ def mlt_paged_attn_decode(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
                                     seq_lens.data_ptr(), O.data_ptr(), float(scale),
                                     _dtype_code(Q), torch.cuda.current_stream(Q.device).cuda_stream)
     if rc != MLT_OK:
-        raise MltError(rc, "mlt_paged_attn_decode", "mlt_gemm_acc")
+        raise MltError(rc, "mlt_paged_attn_decode")
     return O
 
 
