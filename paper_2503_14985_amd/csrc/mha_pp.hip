@@ -208,7 +208,7 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) o_acc[t][r] = 0.f;
   f32x16 s_acc[2];
-  uint32_t pw[16];                   // P^T of the current tile, packed pairs
+  u32x4 pq[4];                       // P^T of the current tile as MFMA operands: one per 16 keys
   float mc_run = -__builtin_inff();  // running maximum of the scores, times c (log2 domain)
   float l_run = 0.f;                 // running sum over this lane's half of the keys
 
@@ -219,21 +219,28 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
   // and one address computation (which the 32 clocks of the running MFMA cover), and every
   // request has about two chunks (2 * NDT MFMAs) of time to arrive.
   V8 fb[2][NDT];
-  // vb / kb: this lane's fragment address plus the slot offset (low bits of the slot offset are
-  // zero, so the XOR that selects the O^T tile / the k slice still only touches chunk bits)
-  auto read_v_frag = [&](int vb, int g, int t, V8& f) {
-    const int off = (vb ^ (t << 6)) + g * 16 * ROWB;
-    const s16x4 lo = lds_read_tr4(smem, off);
-    const s16x4 hi = lds_read_tr4(smem, off + 8 * ROWB);
+  // Fragment addresses are kept as complete LDS addresses in registers, one per XOR variant (the
+  // k slices of K, the 32-row tiles of V^T), and moved from slot to slot by one addition per tile;
+  // everything else about a read is an immediate offset. (Recomputing the XOR per read costs a
+  // vector ALU instruction per MFMA, and the vector ALU is what this kernel is short of.)
+  uint32_t ka[NKK], va[NDT];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) ka[kk] = lds0 + (uint32_t)(k_frag ^ (kk << 5));
+#pragma unroll
+  for (int t = 0; t < NDT; ++t) va[t] = lds0 + (uint32_t)(v_frag ^ (t << 6));
+  auto read_v_frag = [&](int g, int t, V8& f) {
+    const uint32_t a = va[t] + g * 16 * ROWB;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLT_LDS s16x4*)(uintptr_t)a);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLT_LDS s16x4*)(uintptr_t)(a + 8 * ROWB));
     f = join_tr<V8>(lo, hi);
   };
   // K fragment fi of a tile: sub-tile fi & 1 (the two S^T accumulators alternate), k slice fi >> 1
-  auto read_k_frag = [&](int kb, int fi, V8& f) {
-    f = lds_read8<V8>(smem, (kb ^ ((fi >> 1) << 5)) + (fi & 1) * 32 * ROWB);
+  auto read_k_frag = [&](int fi, V8& f) {
+    const uint32_t a = ka[fi >> 1] + (fi & 1) * 32 * ROWB;
+    f = __builtin_bit_cast(V8, *(const MLT_LDS u32x4*)(uintptr_t)a);
   };
   auto mfma_v = [&](int g, int t, const V8& f) {
-    u32x4 p4 = {pw[4 * g], pw[4 * g + 1], pw[4 * g + 2], pw[4 * g + 3]};
-    o_acc[t] = mfma32(f, __builtin_bit_cast(V8, p4), o_acc[t]);
+    o_acc[t] = mfma32(f, __builtin_bit_cast(V8, pq[g]), o_acc[t]);
   };
   auto mfma_k = [&](int fi, const V8& f) {
     if (fi < 2) {                                         // first slice: start from zero
@@ -247,7 +254,7 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
   };
 #define MLT_SB() __builtin_amdgcn_sched_barrier(0)
 
-  // ---- softmax of S_j (in s_acc) -> pw, l_run, mc_run, rescaled o_acc
+  // ---- softmax of S_j (in s_acc) -> pq, mc_run, rescaled o_acc and l_run
   auto softmax_tile = [&](int j) {
     const int kb0 = j * PA_BN;
     // register r of sub-tile kb is key kb0 + 32*kb + 8*(r/4) + 4*h + r%4
@@ -294,9 +301,7 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
         for (int r = 0; r < 16; r += 2) {
           const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r], c, -mc_run));
           const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r + 1], c, -mc_run));
-          const uint32_t w = Elem<Tag>::pack2(p0, p1);
-          pw[8 * kb + r / 2] = w;
-          l_run = Elem<Tag>::add_pair(w, l_run);     // the sum of the ROUNDED weights, as used by P V
+          pq[2 * kb + r / 8][(r / 2) & 3] = Elem<Tag>::pack2(p0, p1);
         }
     }
   };
@@ -322,12 +327,11 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
 
   // prologue: S_0 = K_0 Q^T, then the first two V_0 groups (a compute phase without the P V part)
   {
-    const int kb = k_frag, vb = v_frag;                   // slot 0
-    if (my_nblk > 0) {
+    if (my_nblk > 0) {                                    // ka, va point into slot 0
 #pragma unroll
-      for (int i = 0; i < NDT; ++i) read_k_frag(kb, i, fb[0][i]);
+      for (int i = 0; i < NDT; ++i) read_k_frag(i, fb[0][i]);
 #pragma unroll
-      for (int i = 0; i < NDT; ++i) read_k_frag(kb, NDT + i, fb[1][i]);
+      for (int i = 0; i < NDT; ++i) read_k_frag(NDT + i, fb[1][i]);
       MLT_SB();
 #pragma unroll
       for (int ch = 0; ch < 4; ++ch)
@@ -335,8 +339,8 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
         for (int i = 0; i < NDT; ++i) {
           mfma_k(ch * NDT + i, fb[ch & 1][i]);
           MLT_SB();
-          if (ch < 2) read_k_frag(kb, (ch + 2) * NDT + i, fb[ch & 1][i]);
-          else read_v_frag(vb, ch - 2, i, fb[ch & 1][i]);
+          if (ch < 2) read_k_frag((ch + 2) * NDT + i, fb[ch & 1][i]);
+          else read_v_frag(ch - 2, i, fb[ch & 1][i]);
           MLT_SB();
         }
     }
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
       softmax_tile(j);
       // keep the whole softmax on this side of the barrier (the weights are only consumed after it)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(pw[i]));
+      for (int g = 0; g < 4; ++g) asm volatile("" : "+v"(pq[g]));
     }
     __builtin_amdgcn_sched_barrier(0);
     if (grp == 0) {
@@ -378,21 +382,24 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
     // ---- C_j: O^T += V_j^T P_j^T, then S_{j+1}^T = K_{j+1} Q^T, then the first two groups of
     // V_{j+1} into the buffers for the next compute phase. Chunk n's MFMAs alternate with the
     // reads of chunk n+2: V_j groups 2, 3, then K_{j+1} chunks 0..3, then V_{j+1} groups 0, 1.
-    {
-      const int vb = v_frag + slot_off;
-      const int kb = k_frag + slot_off_next, vbn = v_frag + slot_off_next;
-      if (active) {
+    // On the way the fragment addresses move on to the slot of tile j+1: ka before the first K
+    // read, va after the last V_j read.
+    if (active) {
+      const uint32_t dslot = (uint32_t)(slot_off_next - slot_off);
+      // (on a wavefront's last tile the K reads below fetch fragments nobody uses: cheaper than a
+      // branch per MFMA, and the addresses stay inside the ring)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+      for (int g = 0; g < 4; ++g)
 #pragma unroll
-          for (int t = 0; t < NDT; ++t) {
-            mfma_v(g, t, fb[g & 1][t]);
-            MLT_SB();
-            if (g < 2) read_v_frag(vb, g + 2, t, fb[g & 1][t]);
-            else if (active_next) read_k_frag(kb, (g - 2) * NDT + t, fb[g & 1][t]);
-            MLT_SB();
-          }
-      }
+        for (int t = 0; t < NDT; ++t) {
+          mfma_v(g, t, fb[g & 1][t]);
+          MLT_SB();
+          if (g < 2) read_v_frag(g + 2, t, fb[g & 1][t]);
+          else read_k_frag((g - 2) * NDT + t, fb[g & 1][t]);
+          if (g == 0) { ka[2 * t] += dslot; ka[2 * t + 1] += dslot; }
+          if (g == 3) va[t] += dslot;
+          MLT_SB();
+        }
       if (active_next) {
 #pragma unroll
         for (int ch = 0; ch < 4; ++ch)
@@ -400,11 +407,19 @@ __global__ __launch_bounds__(PA_NT) void mha_pp_kernel(
           for (int i = 0; i < NDT; ++i) {
             mfma_k(ch * NDT + i, fb[ch & 1][i]);
             MLT_SB();
-            if (ch < 2) read_k_frag(kb, (ch + 2) * NDT + i, fb[ch & 1][i]);
-            else read_v_frag(vbn, ch - 2, i, fb[ch & 1][i]);
+            if (ch < 2) read_k_frag((ch + 2) * NDT + i, fb[ch & 1][i]);
+            else read_v_frag(ch - 2, i, fb[ch & 1][i]);
             MLT_SB();
           }
       }
+      // The row sum of the ROUNDED weights (what P V used) is taken here, behind the last MFMA,
+      // while the matrix pipe drains. Measured alternatives: in the softmax phase -5 %; one
+      // addition after each P V MFMA -9 % (dot instructions between MFMAs hold the MFMAs up).
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) l_run = Elem<Tag>::add_pair(pq[g][e], l_run);
+      asm volatile("" : "+v"(l_run));
     }
     if (D == 128) __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
