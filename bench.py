@@ -133,6 +133,31 @@ def paged_decode(binding, ev, dev):
             "workload": "B=%d H=%d S=%d D=%d block=%d bf16, shuffled blocks" % PAGED_SHAPE}
 
 
+def hbm_ceiling(binding, ev, dev):
+    """Rate of a read-only streaming kernel (mlt_probe_hbm_read) over 2 GiB: the practical HBM
+    read rate, context for the memory-bound kernels (`paged_decode`), whose fractions stay
+    quoted against the nominal 8 TB/s."""
+    import torch
+    data = torch.empty(1 << 29, dtype=torch.int32, device=dev).random_(0, 2 ** 31 - 1)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    reps = 10
+    for _ in range(3):
+        binding.mlt_probe_hbm_read(data, sink)
+    e0, e1 = ev.create(), ev.create()
+    binding.mlt_set_timing_events(e0, None)
+    nbytes = binding.mlt_probe_hbm_read(data, sink)
+    binding.mlt_set_timing_events(None, None)
+    for _ in range(reps - 2):
+        binding.mlt_probe_hbm_read(data, sink)
+    binding.mlt_set_timing_events(None, e1)
+    binding.mlt_probe_hbm_read(data, sink)
+    binding.mlt_set_timing_events(None, None)
+    torch.cuda.synchronize()
+    gbs = nbytes * reps / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e9
+    return {"read_GB_per_s": gbs, "frac_hbm_peak": gbs / 8000.0,
+            "note": "read-only streaming kernel over 2 GiB, 16-byte loads, 32 KB pieces round-robin over 8 workgroups per CU"}
+
+
 def mfma_ceiling(binding, ev, A, dev):
     """Rate of a register-only MFMA loop over the whole chip (mlt_probe_mfma) on all-zero operands
     and on the GEMM's own N(0,1) operand values: the second is what the chip's power management
@@ -292,6 +317,7 @@ def main():
     if not args.no_ceiling:
         out["mfma_ceiling"] = mfma_ceiling(binding, ev, A, dev)
         out["paged_decode"] = paged_decode(binding, ev, dev)
+        out["hbm_ceiling"] = hbm_ceiling(binding, ev, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(A_h, B_h, Q_h, K_h, V_h, scale)
     print(json.dumps(out))

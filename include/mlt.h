@@ -122,6 +122,18 @@ int mlt_paged_attn_decode(int64_t B, int64_t H, int64_t D, int64_t block_size, i
 int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* stream);
 
 /*
+ * Diagnostic for benchmarks (not part of the paper's method): enqueues one kernel that reads
+ * `bytes` bytes at `data` once with 16-byte loads from every CU and writes nothing. On a buffer
+ * much larger than the caches its duration gives the practical HBM read rate, the ceiling for
+ * the memory-bound kernels here (paged-attention decode, skinny GEMM).
+ *   data    device, 16-byte aligned, `bytes` bytes (a positive multiple of 16); only read
+ *   sink    device, at least 4 bytes (never written in practice; keeps the loads alive)
+ * Returns MLT_OK, MLT_ERR_INVALID_ARG (null pointer, bad size or alignment) or a launch/device
+ * error.
+ */
+int mlt_probe_hbm_read(const void* data, int64_t bytes, void* sink, void* stream);
+
+/*
  * Per-kernel timing hook for benchmarks: when `start_event`/`stop_event` (hipEvent_t as void*,
  * may be NULL) are set, the next launches made by this thread record them on the launch stream
  * immediately before the first and after the last kernel of one entry-point call. Pass NULLs to

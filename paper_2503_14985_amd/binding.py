@@ -20,7 +20,7 @@ MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE
 
 EXPORTS = ("mlt_gemm", "mlt_mha_fwd", "mlt_set_timing_events", "mlt_last_kernel",
            "mlt_query_tiling", "mlt_status_string", "mlt_version", "mlt_probe_mfma",
-           "mlt_paged_attn_decode", "mlt_gemm_acc")
+           "mlt_paged_attn_decode", "mlt_gemm_acc", "mlt_probe_hbm_read")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -41,6 +41,8 @@ _lib.mlt_paged_attn_decode.argtypes = [_i64, _i64, _i64, _i64, _i64, _i64, _p, _
                                        ctypes.c_float, _i32, _p]
 _lib.mlt_probe_mfma.restype = _i32
 _lib.mlt_probe_mfma.argtypes = [_i32, _p, _p, ctypes.POINTER(ctypes.c_double), _p]
+_lib.mlt_probe_hbm_read.restype = _i32
+_lib.mlt_probe_hbm_read.argtypes = [_p, _i64, _p, _p]
 _lib.mlt_set_timing_events.restype = None
 _lib.mlt_set_timing_events.argtypes = [_p, _p]
 _lib.mlt_last_kernel.restype = ctypes.c_char_p
@@ -112,6 +114,19 @@ def mlt_probe_mfma(iters: int, data: torch.Tensor, sink: torch.Tensor) -> float:
     if rc != MLT_OK:
         raise MltError(rc, "mlt_probe_mfma")
     return flop.value
+
+
+def mlt_probe_hbm_read(data: torch.Tensor, sink: torch.Tensor) -> int:
+    """Enqueue the read-only streaming kernel over `data` (contiguous GPU tensor, a multiple of 16
+    bytes) on the current stream; returns the bytes it reads."""
+    nbytes = data.numel() * data.element_size()
+    if not data.is_cuda or not data.is_contiguous():
+        raise ValueError("mlt_probe_hbm_read: data must be a contiguous GPU tensor")
+    rc = _lib.mlt_probe_hbm_read(data.data_ptr(), nbytes, sink.data_ptr(),
+                                 torch.cuda.current_stream(data.device).cuda_stream)
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_probe_hbm_read")
+    return nbytes
 
 
 def mlt_query_tiling(op: int, dims, dtype: int):

@@ -189,6 +189,27 @@ int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* 
   return MLT_OK;
 }
 
+int mlt_probe_hbm_read(const void* data, int64_t bytes, void* sink, void* stream) {
+  if (!data || !sink || bytes < 16 || bytes % 16 != 0 ||
+      (reinterpret_cast<uintptr_t>(data) & 15) != 0)
+    return MLT_ERR_INVALID_ARG;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  int dev = 0, ncu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return MLT_ERR_DEVICE;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  int rc;
+  {
+    TimedRegion t(s);
+    rc = run_hbm_read_probe(data, bytes, (uint32_t*)sink, ncu, s);
+  }
+  if (rc == MLT_OK) g_last_kernel = "hbm_read_probe";
+  return rc;
+}
+
 void mlt_set_timing_events(void* start_event, void* stop_event) {
   g_ev_start = (hipEvent_t)start_event;
   g_ev_stop = (hipEvent_t)stop_event;

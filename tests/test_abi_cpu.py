@@ -66,6 +66,12 @@ def test_probe_argument_validation_without_device(binding):
     assert f(16, None, p, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG      # data null
     assert f(16, p, None, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG      # sink null
     assert f(16, p, p, None, None) == binding.MLT_ERR_INVALID_ARG                       # flop null
+    r = lib.mlt_probe_hbm_read
+    assert r(None, 1024, p, None) == binding.MLT_ERR_INVALID_ARG                        # data null
+    assert r(p, 1024, None, None) == binding.MLT_ERR_INVALID_ARG                        # sink null
+    assert r(p, 0, p, None) == binding.MLT_ERR_INVALID_ARG                              # empty
+    assert r(p, 1000, p, None) == binding.MLT_ERR_INVALID_ARG                           # not a multiple of 16
+    assert r(ctypes.c_void_p(0x1008), 1024, p, None) == binding.MLT_ERR_INVALID_ARG     # misaligned
 
 
 def test_skinny_shapes_are_routed_by_the_tiling_query(binding):
