@@ -406,7 +406,16 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.bm = 64; p.bn = 64; p.bk = 32; p.wm = 2; p.wn = 2;
     return p;
   }
-  if ((g.forced == GEMM_AUTO || g.forced == GEMM_SKINNY) && gemm_skinny_ok(g)) {
+  // Streaming variant: measured faster for one 16-row tile of A (A is re-read from L2 per column
+  // block, which costs more the taller A is) once B is well beyond the caches.
+  const bool stream_auto = g.forced == GEMM_AUTO && g.M <= 16 && g.N * g.K >= ((int64_t)1 << 25);
+  if ((g.forced == GEMM_SKINNY_DMA || stream_auto) && gemm_skinny_dma_ok(g)) {
+    p.variant = GEMM_SKINNY_DMA; p.name = "gemm_nt_skinny_16cols_stream";
+    p.bm = (int)((g.M + 15) / 16) * 16; p.bn = 16; p.bk = 512; p.wm = 1; p.wn = 1;
+    p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
+    return p;
+  }
+  if ((g.forced == GEMM_AUTO || g.forced == GEMM_SKINNY || g.forced == GEMM_SKINNY_DMA) && gemm_skinny_ok(g)) {
     p.variant = GEMM_SKINNY; p.name = "gemm_nt_skinny_16cols_ksplit8";
     p.bm = (int)((g.M + 15) / 16) * 16; p.bn = 16; p.bk = 32; p.wm = 1; p.wn = 1;
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
@@ -415,7 +424,9 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   // Big tile when it still fills the chip, otherwise the small one.
   const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
   int v = tiles256 >= 192 ? (gemm_pp_ok(g) ? GEMM_256_PP : GEMM_256_W8) : GEMM_128;
-  if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS && g.forced != GEMM_SKINNY) v = g.forced;
+  if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS && g.forced != GEMM_SKINNY &&
+      g.forced != GEMM_SKINNY_DMA)
+    v = g.forced;
   if (v == GEMM_256_PP && !gemm_pp_ok(g)) v = GEMM_256_W8;
   p.variant = v;
   p.bk = 64;
@@ -457,6 +468,7 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_128: return launch_tile_tb<Tag, 128, 128, 64, 2, 2>(g, s);
     case GEMM_256_PP: return run_gemm_pp(g, s);
     case GEMM_SKINNY: return run_gemm_skinny(g, s);
+    case GEMM_SKINNY_DMA: return run_gemm_skinny_dma(g, s);
   }
   return MLT_ERR_UNSUPPORTED;
 }

@@ -144,6 +144,218 @@ int run_skinny_t(const GemmArgs& g, hipStream_t s) {
   return MLT_ERR_UNSUPPORTED;
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Streaming variant for large B. What limits the kernel above on matrices far beyond the caches
+// is the shape of its HBM requests: one load instruction touches 16 rows with 64 bytes each. Here
+// every load instruction fetches 1 KB of ONE row of B (global_load_lds_dwordx4: 64 lanes x 16
+// contiguous bytes, straight into LDS), which is the request shape that reaches the chip's read
+// ceiling, and a deep ring keeps 112 KB per CU in flight.
+//   * a workgroup owns 16 columns of C (16 rows of the stored B) and all of K; a stage is the 512
+//     k values (1 KB) of each of the 16 rows; the LDS ring holds 8 stages (128 KB);
+//   * wavefronts 0-3 only fetch: wavefront p loads rows 4p .. 4p+3 of every stage, seven stages
+//     ahead. Their vector-memory counter sees nothing but these loads, so "stage s has landed" is
+//     an exact count; wavefronts 4-7 only compute: each takes four of the stage's sixteen 32-wide
+//     k chunks, reads the B fragment from LDS and the A fragments from global memory (A is at
+//     most 64 rows and stays in L2; their loads are counted by the compiler as usual);
+//   * one workgroup barrier per stage; the slot of stage s-1 is refilled right after barrier s;
+//   * workgroups are persistent (one per CU) and walk over their column blocks without letting
+//     the ring drain; at the end of a block the four partial tiles are added through a separate
+//     LDS area (one more barrier) and stored;
+//   * within a row's 1 KB the 16-byte chunks are stored permuted (chunk c at position c ^ row):
+//     the source address of a lane is free, its LDS position is not, and the 16 lanes that read
+//     rows 0..15 at one k position must hit 16 distinct bank groups.
+constexpr int SD_ST = 8;              // ring stages
+constexpr int SD_KS = 512;            // k values per stage
+constexpr int SD_STAGE_B = 16 * SD_KS * 2;
+constexpr int SD_SMEM = SD_ST * SD_STAGE_B;
+constexpr int SD_RED = 4 * SK_MAXMT * 256 * 4;   // reduction area behind the ring
+
+constexpr int sd_wait_imm(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (15 << 8); }
+
+__device__ __forceinline__ void sd_load_lds16(const void* base, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(base)
+               : "memory", "m0");
+}
+
+template <typename Tag, int MT>
+__global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
+    int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
+    const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc) {
+  typedef typename Elem<Tag>::vec8 V8;
+  extern __shared__ __align__(16) char smem[];             // the ring, then the reduction area
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int NS = (K + SD_KS - 1) / SD_KS;                  // stages per column block
+  const int nblocks = (N + 15) / 16;
+  // Persistent workgroups: this one owns column blocks blockIdx.x, + gridDim.x, ...; their stages
+  // form one stream g = 0 .. G-1 (block g / NS, k stage g % NS), so the ring never drains between
+  // blocks.
+  const int nmine = (nblocks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int G = nmine * NS;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
+
+  if (wave < 4) {
+    // ---- fetching wavefronts
+    auto issue_stage = [&](int g) {
+      const int bi = g / NS, ks = g - bi * NS;
+      const int n0 = ((int)blockIdx.x + bi * (int)gridDim.x) * 16;
+      const int k0 = ks * SD_KS;
+      const char* Bw = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
+      const uint32_t slot = lds0 + (uint32_t)(g % SD_ST) * SD_STAGE_B;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = wave * 4 + i;
+        const int nrow = n0 + r < N ? r : N - 1 - n0;      // clamped: such columns are never stored
+        int ck = lane ^ r;                                 // the 16-byte chunk this lane fetches
+        if (k0 + ck * 8 >= K) ck = 0;                      // past K (last stage): any valid chunk, zeroed later
+        sd_load_lds16(Bw, (uint32_t)nrow * (uint32_t)ldb * 2u + (uint32_t)(k0 + ck * 8) * 2u,
+                      slot + (uint32_t)r * 1024u);
+      }
+    };
+#pragma unroll
+    for (int g = 0; g < SD_ST - 1; ++g)
+      if (g < G) issue_stage(g);
+    int ks = 0;
+    for (int g = 0; g < G; ++g) {
+      // issued so far: stages 0 .. min(G, g + SD_ST - 1) - 1; those after g may stay in flight
+      const int last = g + SD_ST - 2 < G - 1 ? g + SD_ST - 2 : G - 1;
+      switch (last - g) {
+        case 0: __builtin_amdgcn_s_waitcnt(sd_wait_imm(0)); break;
+        case 1: __builtin_amdgcn_s_waitcnt(sd_wait_imm(4)); break;
+        case 2: __builtin_amdgcn_s_waitcnt(sd_wait_imm(8)); break;
+        case 3: __builtin_amdgcn_s_waitcnt(sd_wait_imm(12)); break;
+        case 4: __builtin_amdgcn_s_waitcnt(sd_wait_imm(16)); break;
+        case 5: __builtin_amdgcn_s_waitcnt(sd_wait_imm(20)); break;
+        default: __builtin_amdgcn_s_waitcnt(sd_wait_imm(24)); break;
+      }
+      __builtin_amdgcn_s_barrier();                        // stage g is complete in LDS for everyone
+      if (g + SD_ST - 1 < G) issue_stage(g + SD_ST - 1);   // into the slot of stage g-1, read before this barrier
+      if (++ks == NS) {                                    // end of a column block: the reduction's barrier
+        ks = 0;
+        __syncthreads();
+      }
+    }
+  } else {
+    // ---- computing wavefronts
+    const int cw = wave - 4, ctid = tid - 256;
+    const int r16 = lane & 15, q = lane >> 4;
+    float* red = reinterpret_cast<float*>(smem + SD_SMEM);  // [4][MT][256]
+    const uint16_t* ap[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int arow = mt * 16 + r16 < M ? mt * 16 + r16 : M - 1;
+      ap[mt] = A + (int64_t)arow * lda;
+    }
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // A fragments of k stage ks: chunk 4*cw + j, k = ks*512 + (4*cw + j)*32 + 8*q
+    auto load_a = [&](int ks, u32x4 (&af)[4][MT]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = ks * SD_KS + (4 * cw + j) * 32 + 8 * q;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          af[j][mt] = *reinterpret_cast<const u32x4_mem*>(ap[mt] + (k < K ? k : 0));
+      }
+    };
+    int ks = 0, bi = 0;
+    // one stage: `cur` holds its A fragments, those of the next stage are requested into `nxt`
+    auto step = [&](int g, u32x4 (&cur)[4][MT], u32x4 (&nxt)[4][MT]) __attribute__((always_inline)) {
+      __builtin_amdgcn_s_barrier();
+      const uint32_t slot = lds0 + (uint32_t)(g % SD_ST) * SD_STAGE_B;
+      u32x4 bf[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c16 = (4 * cw + j) * 4 + q;                // 16-byte chunk of the row piece
+        bf[j] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(slot + (uint32_t)r16 * 1024u + (uint32_t)((c16 ^ r16) << 4));
+      }
+      load_a(ks + 1 < NS ? ks + 1 : 0, nxt);               // unconditional: keeps the load counting exact
+      const bool whole = (ks + 1) * SD_KS <= K;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool dead = !whole && ks * SD_KS + (4 * cw + j) * 32 + 8 * q >= K;
+        const u32x4 b = dead ? zero4 : bf[j];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const u32x4 a = dead ? zero4 : cur[j][mt];
+          acc[mt] = mfma16(__builtin_bit_cast(V8, a), __builtin_bit_cast(V8, b), acc[mt]);
+        }
+      }
+      if (++ks == NS) {
+        // end of a column block: the four partial tiles meet in LDS, 256 lanes add them and store
+        ks = 0;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            red[(cw * MT + mt) * 256 + (4 * q + r) * 16 + r16] = acc[mt][r];
+            acc[mt][r] = 0.f;
+          }
+        __syncthreads();                                     // with the fence: the partial tiles are LDS stores
+        const int n0 = ((int)blockIdx.x + bi * (int)gridDim.x) * 16;
+        ++bi;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          float sum = 0.f;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) sum += red[(w * MT + mt) * 256 + ctid];
+          const int gr = mt * 16 + (ctid >> 4), gc = n0 + (ctid & 15);
+          if (gr < M && gc < N) C[(int64_t)gr * ldc + gc] = Elem<Tag>::from_f32(sum);
+        }
+      }
+    };
+    u32x4 af0[4][MT], af1[4][MT];
+    load_a(0, af0);
+    for (int g = 0; g < G; g += 2) {
+      step(g, af0, af1);
+      if (g + 1 < G) step(g + 1, af1, af0);
+    }
+  }
+}
+
+template <typename Tag, int MT>
+int launch_skinny_dma(const GemmArgs& g, hipStream_t s) {
+  auto kern = gemm_skinny_dma_kernel<Tag, MT>;
+  static thread_local int configured_dev = -1;            // opt in to > 64 KB LDS once per device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
+  if (configured_dev != dev) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            SD_SMEM + SD_RED) != hipSuccess) {
+      (void)hipGetLastError();
+      return MLT_ERR_LAUNCH;
+    }
+    configured_dev = dev;
+  }
+  static thread_local int ncu = 0;
+  if (ncu == 0 && hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    ncu = 0;
+    return MLT_ERR_DEVICE;
+  }
+  const int64_t nblocks = (g.N + 15) / 16;
+  const unsigned nwg = (unsigned)(nblocks < ncu ? nblocks : ncu);   // one persistent workgroup per CU
+  hipLaunchKernelGGL(kern, dim3(nwg), dim3(SK_NT), SD_SMEM + SD_RED, s, (int)g.M, (int)g.N, (int)g.K,
+                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc);
+  return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
+}
+
+template <typename Tag>
+int run_skinny_dma_t(const GemmArgs& g, hipStream_t s) {
+  switch ((g.M + 15) / 16) {
+    case 1: return launch_skinny_dma<Tag, 1>(g, s);
+    case 2: return launch_skinny_dma<Tag, 2>(g, s);
+    case 3: return launch_skinny_dma<Tag, 3>(g, s);
+    case 4: return launch_skinny_dma<Tag, 4>(g, s);
+  }
+  return MLT_ERR_UNSUPPORTED;
+}
+
 }  // namespace
 
 // Worth it only when the columns alone fill the chip (one workgroup per 16 columns).
@@ -157,6 +369,15 @@ bool gemm_skinny_ok(const GemmArgs& g) {
 
 int run_gemm_skinny(const GemmArgs& g, hipStream_t s) {
   return g.dtype == MLT_BF16 ? run_skinny_t<bf16_tag>(g, s) : run_skinny_t<f16_tag>(g, s);
+}
+
+// The streaming variant addresses B rows with 32-bit byte offsets from the workgroup's first row.
+bool gemm_skinny_dma_ok(const GemmArgs& g) {
+  return gemm_skinny_ok(g) && g.ldb * 2 * 16 + g.K * 2 < ((int64_t)1 << 32);
+}
+
+int run_gemm_skinny_dma(const GemmArgs& g, hipStream_t s) {
+  return g.dtype == MLT_BF16 ? run_skinny_dma_t<bf16_tag>(g, s) : run_skinny_dma_t<f16_tag>(g, s);
 }
 
 }  // namespace mlt
