@@ -406,16 +406,23 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.bm = 64; p.bn = 64; p.bk = 32; p.wm = 2; p.wn = 2;
     return p;
   }
-  // Streaming variant: measured faster for one 16-row tile of A (A is re-read from L2 per column
-  // block, which costs more the taller A is) once B is well beyond the caches.
-  const bool stream_auto = g.forced == GEMM_AUTO && g.M <= 16 && g.N * g.K >= ((int64_t)1 << 25);
-  if ((g.forced == GEMM_SKINNY_DMA || stream_auto) && gemm_skinny_dma_ok(g)) {
-    p.variant = GEMM_SKINNY_DMA; p.name = "gemm_nt_skinny_16cols_stream";
-    p.bm = (int)((g.M + 15) / 16) * 16; p.bn = 16; p.bk = 512; p.wm = 1; p.wn = 1;
+  // Streaming variants (B through an LDS ring): worth it once B is well beyond the caches. One
+  // 16-row tile of A: 16 columns x 512 k per stage (the better HBM request shape); taller A: 64
+  // columns x 128 k (every A fragment, re-read from L2 per column block, serves four column
+  // tiles), provided 64-column blocks still fill the chip.
+  const bool stream_auto = g.forced == GEMM_AUTO && g.N * g.K >= ((int64_t)1 << 25);
+  const bool want_wide = g.forced == GEMM_SKINNY_DMAW || (stream_auto && g.M > 16 && g.N >= 16384);
+  const bool want_narrow = g.forced == GEMM_SKINNY_DMA || (stream_auto && !want_wide && g.M <= 16);
+  if ((want_wide || want_narrow) && gemm_skinny_dma_ok(g)) {
+    p.variant = want_wide ? GEMM_SKINNY_DMAW : GEMM_SKINNY_DMA;
+    p.name = want_wide ? "gemm_nt_skinny_64cols_stream" : "gemm_nt_skinny_16cols_stream";
+    p.bm = (int)((g.M + 15) / 16) * 16; p.bn = want_wide ? 64 : 16; p.bk = want_wide ? 128 : 512;
+    p.wm = 1; p.wn = 1;
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
     return p;
   }
-  if ((g.forced == GEMM_AUTO || g.forced == GEMM_SKINNY || g.forced == GEMM_SKINNY_DMA) && gemm_skinny_ok(g)) {
+  if ((g.forced == GEMM_AUTO || g.forced == GEMM_SKINNY || g.forced == GEMM_SKINNY_DMA ||
+       g.forced == GEMM_SKINNY_DMAW) && gemm_skinny_ok(g)) {
     p.variant = GEMM_SKINNY; p.name = "gemm_nt_skinny_16cols_ksplit8";
     p.bm = (int)((g.M + 15) / 16) * 16; p.bn = 16; p.bk = 32; p.wm = 1; p.wn = 1;
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
@@ -425,7 +432,7 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
   int v = tiles256 >= 192 ? (gemm_pp_ok(g) ? GEMM_256_PP : GEMM_256_W8) : GEMM_128;
   if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS && g.forced != GEMM_SKINNY &&
-      g.forced != GEMM_SKINNY_DMA)
+      g.forced != GEMM_SKINNY_DMA && g.forced != GEMM_SKINNY_DMAW)
     v = g.forced;
   if (v == GEMM_256_PP && !gemm_pp_ok(g)) v = GEMM_256_W8;
   p.variant = v;
@@ -468,7 +475,8 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_128: return launch_tile_tb<Tag, 128, 128, 64, 2, 2>(g, s);
     case GEMM_256_PP: return run_gemm_pp(g, s);
     case GEMM_SKINNY: return run_gemm_skinny(g, s);
-    case GEMM_SKINNY_DMA: return run_gemm_skinny_dma(g, s);
+    case GEMM_SKINNY_DMA: return run_gemm_skinny_dma(g, false, s);
+    case GEMM_SKINNY_DMAW: return run_gemm_skinny_dma(g, true, s);
   }
   return MLT_ERR_UNSUPPORTED;
 }

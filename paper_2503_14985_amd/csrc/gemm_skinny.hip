@@ -147,29 +147,39 @@ int run_skinny_t(const GemmArgs& g, hipStream_t s) {
 
 // ---------------------------------------------------------------------------------------------
 // Streaming variant for large B. What limits the kernel above on matrices far beyond the caches
-// is the shape of its HBM requests: one load instruction touches 16 rows with 64 bytes each. Here
-// every load instruction fetches 1 KB of ONE row of B (global_load_lds_dwordx4: 64 lanes x 16
-// contiguous bytes, straight into LDS), which is the request shape that reaches the chip's read
-// ceiling, and a deep ring keeps 112 KB per CU in flight.
-//   * a workgroup owns 16 columns of C (16 rows of the stored B) and all of K; a stage is the 512
-//     k values (1 KB) of each of the 16 rows; the LDS ring holds 8 stages (128 KB);
-//   * wavefronts 0-3 only fetch: wavefront p loads rows 4p .. 4p+3 of every stage, seven stages
-//     ahead. Their vector-memory counter sees nothing but these loads, so "stage s has landed" is
-//     an exact count; wavefronts 4-7 only compute: each takes four of the stage's sixteen 32-wide
-//     k chunks, reads the B fragment from LDS and the A fragments from global memory (A is at
-//     most 64 rows and stays in L2; their loads are counted by the compiler as usual);
+// is the shape of its HBM requests (one load instruction touches 16 rows with 64 bytes each) and,
+// for taller A, that A is fetched from L2 again for every 16 columns. Here B goes through an LDS
+// ring in long contiguous row pieces and stays 7 stages (112 KB per CU) in flight:
+//   * a stage is 16 KB of B: in the narrow form 16 rows x 512 k (1 KB per row, one row per load
+//     instruction: 64 lanes x 16 contiguous bytes, global_load_lds_dwordx4), in the wide form
+//     64 rows x 128 k (256 bytes per row, four rows per load instruction). The narrow form has
+//     the better request shape; the wide form reuses every A fragment for four column tiles, which
+//     matters once A has more than one 16-row tile. The ring holds 8 stages (128 KB);
+//   * wavefronts 0-3 only fetch: wavefront p issues load instructions 4p .. 4p+3 of every stage,
+//     seven stages ahead. Their vector-memory counter sees nothing but these loads, so "stage s
+//     has landed" is an exact count; wavefronts 4-7 only compute: they split the 32-wide k chunks
+//     of a stage among themselves, read the B fragments from LDS and the A fragments from global
+//     memory (A stays in L2; their loads are counted by the compiler as usual);
 //   * one workgroup barrier per stage; the slot of stage s-1 is refilled right after barrier s;
 //   * workgroups are persistent (one per CU) and walk over their column blocks without letting
 //     the ring drain; at the end of a block the four partial tiles are added through a separate
-//     LDS area (one more barrier) and stored;
-//   * within a row's 1 KB the 16-byte chunks are stored permuted (chunk c at position c ^ row):
-//     the source address of a lane is free, its LDS position is not, and the 16 lanes that read
-//     rows 0..15 at one k position must hit 16 distinct bank groups.
+//     LDS area and stored;
+//   * within a row piece the 16-byte chunks are stored permuted (chunk c at position c ^ (row &
+//     15)): the source address of a lane is free, its LDS position is not, and the 16 lanes that
+//     read 16 rows at one k position must hit 16 distinct bank groups.
 constexpr int SD_ST = 8;              // ring stages
-constexpr int SD_KS = 512;            // k values per stage
-constexpr int SD_STAGE_B = 16 * SD_KS * 2;
+constexpr int SD_STAGE_B = 16384;     // bytes of B per stage
 constexpr int SD_SMEM = SD_ST * SD_STAGE_B;
-constexpr int SD_RED = 4 * SK_MAXMT * 256 * 4;   // reduction area behind the ring
+constexpr int SD_RED = 4 * 4 * 256 * 4;   // reduction area behind the ring: [4 wavefronts][4 tiles][256]
+
+template <bool WIDE> struct SdCfg {
+  static constexpr int RPS = WIDE ? 64 : 16;     // rows of B (columns of C) per stage and column block
+  static constexpr int KS = WIDE ? 128 : 512;    // k values per stage
+  static constexpr int PB = KS * 2;              // bytes of a row piece
+  static constexpr int LPR = PB / 16;            // lanes per row piece
+  static constexpr int NT = RPS / 16;            // 16-column tiles per block
+  static constexpr int J = KS / 32 / 4;          // k chunks per computing wavefront and stage
+};
 
 constexpr int sd_wait_imm(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (15 << 8); }
 
@@ -180,16 +190,18 @@ __device__ __forceinline__ void sd_load_lds16(const void* base, uint32_t voff, u
                : "memory", "m0");
 }
 
-template <typename Tag, int MT>
+template <typename Tag, int MT, bool WIDE>
 __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc) {
   typedef typename Elem<Tag>::vec8 V8;
+  typedef SdCfg<WIDE> L;
+  constexpr int KS = L::KS, NT = L::NT, J = L::J;
   extern __shared__ __align__(16) char smem[];             // the ring, then the reduction area
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int NS = (K + SD_KS - 1) / SD_KS;                  // stages per column block
-  const int nblocks = (N + 15) / 16;
+  const int NS = (K + KS - 1) / KS;                        // stages per column block
+  const int nblocks = (N + L::RPS - 1) / L::RPS;
   // Persistent workgroups: this one owns column blocks blockIdx.x, + gridDim.x, ...; their stages
   // form one stream g = 0 .. G-1 (block g / NS, k stage g % NS), so the ring never drains between
   // blocks.
@@ -198,21 +210,24 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
 
   if (wave < 4) {
-    // ---- fetching wavefronts
+    // ---- fetching wavefronts: load instruction ii of a stage fills LDS bytes ii*1024 .. +1023 of
+    // the slot, i.e. rows ii*(64/LPR) .. of the stage; lane l serves row l / LPR of those at
+    // position l % LPR
     auto issue_stage = [&](int g) {
       const int bi = g / NS, ks = g - bi * NS;
-      const int n0 = ((int)blockIdx.x + bi * (int)gridDim.x) * 16;
-      const int k0 = ks * SD_KS;
+      const int n0 = ((int)blockIdx.x + bi * (int)gridDim.x) * L::RPS;
+      const int k0 = ks * KS;
       const char* Bw = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
       const uint32_t slot = lds0 + (uint32_t)(g % SD_ST) * SD_STAGE_B;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int r = wave * 4 + i;
+        const int ii = wave * 4 + i;
+        const int r = ii * (64 / L::LPR) + lane / L::LPR;
         const int nrow = n0 + r < N ? r : N - 1 - n0;      // clamped: such columns are never stored
-        int ck = lane ^ r;                                 // the 16-byte chunk this lane fetches
+        int ck = (lane % L::LPR) ^ (r & 15);               // the 16-byte chunk this lane fetches
         if (k0 + ck * 8 >= K) ck = 0;                      // past K (last stage): any valid chunk, zeroed later
         sd_load_lds16(Bw, (uint32_t)nrow * (uint32_t)ldb * 2u + (uint32_t)(k0 + ck * 8) * 2u,
-                      slot + (uint32_t)r * 1024u);
+                      slot + (uint32_t)ii * 1024u);
       }
     };
 #pragma unroll
@@ -233,16 +248,17 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
       }
       __builtin_amdgcn_s_barrier();                        // stage g is complete in LDS for everyone
       if (g + SD_ST - 1 < G) issue_stage(g + SD_ST - 1);   // into the slot of stage g-1, read before this barrier
-      if (++ks == NS) {                                    // end of a column block: the reduction's barrier
+      if (++ks == NS) {                                    // end of a column block: the reduction's barriers
         ks = 0;
-        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < 2 * MT - 1; ++b) __syncthreads();
       }
     }
   } else {
-    // ---- computing wavefronts
+    // ---- computing wavefronts: wavefront cw takes k chunks J*cw .. J*cw + J-1 of every stage
     const int cw = wave - 4, ctid = tid - 256;
     const int r16 = lane & 15, q = lane >> 4;
-    float* red = reinterpret_cast<float*>(smem + SD_SMEM);  // [4][MT][256]
+    float* red = reinterpret_cast<float*>(smem + SD_SMEM);  // [4][NT][256]
     const uint16_t* ap[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -250,14 +266,16 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
       ap[mt] = A + (int64_t)arow * lda;
     }
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    f32x4 acc[MT];
+    f32x4 acc[MT][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // A fragments of k stage ks: chunk 4*cw + j, k = ks*512 + (4*cw + j)*32 + 8*q
-    auto load_a = [&](int ks, u32x4 (&af)[4][MT]) __attribute__((always_inline)) {
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int k = ks * SD_KS + (4 * cw + j) * 32 + 8 * q;
+      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // A fragments of k stage ks: k = ks*KS + (J*cw + j)*32 + 8*q
+    auto load_a = [&](int ks, u32x4 (&af)[J][MT]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int j = 0; j < J; ++j) {
+        const int k = ks * KS + (J * cw + j) * 32 + 8 * q;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
           af[j][mt] = *reinterpret_cast<const u32x4_mem*>(ap[mt] + (k < K ? k : 0));
@@ -265,51 +283,62 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
     };
     int ks = 0, bi = 0;
     // one stage: `cur` holds its A fragments, those of the next stage are requested into `nxt`
-    auto step = [&](int g, u32x4 (&cur)[4][MT], u32x4 (&nxt)[4][MT]) __attribute__((always_inline)) {
+    auto step = [&](int g, u32x4 (&cur)[J][MT], u32x4 (&nxt)[J][MT]) __attribute__((always_inline)) {
       __builtin_amdgcn_s_barrier();
       const uint32_t slot = lds0 + (uint32_t)(g % SD_ST) * SD_STAGE_B;
-      u32x4 bf[4];
+      u32x4 bf[J][NT];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int c16 = (4 * cw + j) * 4 + q;                // 16-byte chunk of the row piece
-        bf[j] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(slot + (uint32_t)r16 * 1024u + (uint32_t)((c16 ^ r16) << 4));
+      for (int j = 0; j < J; ++j) {
+        const int c16 = (J * cw + j) * 4 + q;                // 16-byte chunk of the row piece
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          bf[j][nt] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(
+              slot + (uint32_t)(nt * 16 + r16) * L::PB + (uint32_t)((c16 ^ r16) << 4));
       }
       load_a(ks + 1 < NS ? ks + 1 : 0, nxt);               // unconditional: keeps the load counting exact
-      const bool whole = (ks + 1) * SD_KS <= K;
+      const bool whole = (ks + 1) * KS <= K;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const bool dead = !whole && ks * SD_KS + (4 * cw + j) * 32 + 8 * q >= K;
-        const u32x4 b = dead ? zero4 : bf[j];
+      for (int j = 0; j < J; ++j) {
+        const bool dead = !whole && ks * KS + (J * cw + j) * 32 + 8 * q >= K;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           const u32x4 a = dead ? zero4 : cur[j][mt];
-          acc[mt] = mfma16(__builtin_bit_cast(V8, a), __builtin_bit_cast(V8, b), acc[mt]);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            const u32x4 b = dead ? zero4 : bf[j][nt];
+            acc[mt][nt] = mfma16(__builtin_bit_cast(V8, a), __builtin_bit_cast(V8, b), acc[mt][nt]);
+          }
         }
       }
       if (++ks == NS) {
-        // end of a column block: the four partial tiles meet in LDS, 256 lanes add them and store
+        // end of a column block: per 16-row tile of A the four wavefronts' partial tiles meet in
+        // LDS, 256 lanes add them and store (2*MT - 1 barriers, matched by the fetching wavefronts)
         ks = 0;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            red[(cw * MT + mt) * 256 + (4 * q + r) * 16 + r16] = acc[mt][r];
-            acc[mt][r] = 0.f;
-          }
-        __syncthreads();                                     // with the fence: the partial tiles are LDS stores
-        const int n0 = ((int)blockIdx.x + bi * (int)gridDim.x) * 16;
+        const int n0 = ((int)blockIdx.x + bi * (int)gridDim.x) * L::RPS;
         ++bi;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          float sum = 0.f;
+          if (mt > 0) __syncthreads();                       // the previous tile's sums have been read
 #pragma unroll
-          for (int w = 0; w < 4; ++w) sum += red[(w * MT + mt) * 256 + ctid];
-          const int gr = mt * 16 + (ctid >> 4), gc = n0 + (ctid & 15);
-          if (gr < M && gc < N) C[(int64_t)gr * ldc + gc] = Elem<Tag>::from_f32(sum);
+          for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              red[(cw * NT + nt) * 256 + (4 * q + r) * 16 + r16] = acc[mt][nt][r];
+              acc[mt][nt][r] = 0.f;
+            }
+          __syncthreads();                                   // with the fence: the partial tiles are LDS stores
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sum += red[(w * NT + nt) * 256 + ctid];
+            const int gr = mt * 16 + (ctid >> 4), gc = n0 + nt * 16 + (ctid & 15);
+            if (gr < M && gc < N) C[(int64_t)gr * ldc + gc] = Elem<Tag>::from_f32(sum);
+          }
         }
       }
     };
-    u32x4 af0[4][MT], af1[4][MT];
+    u32x4 af0[J][MT], af1[J][MT];
     load_a(0, af0);
     for (int g = 0; g < G; g += 2) {
       step(g, af0, af1);
@@ -318,40 +347,36 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
   }
 }
 
-template <typename Tag, int MT>
+template <typename Tag, int MT, bool WIDE>
 int launch_skinny_dma(const GemmArgs& g, hipStream_t s) {
-  auto kern = gemm_skinny_dma_kernel<Tag, MT>;
+  auto kern = gemm_skinny_dma_kernel<Tag, MT, WIDE>;
   static thread_local int configured_dev = -1;            // opt in to > 64 KB LDS once per device
+  static thread_local int ncu = 0;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
   if (configured_dev != dev) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            SD_SMEM + SD_RED) != hipSuccess) {
+                            SD_SMEM + SD_RED) != hipSuccess ||
+        hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
       (void)hipGetLastError();
       return MLT_ERR_LAUNCH;
     }
     configured_dev = dev;
   }
-  static thread_local int ncu = 0;
-  if (ncu == 0 && hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
-    (void)hipGetLastError();
-    ncu = 0;
-    return MLT_ERR_DEVICE;
-  }
-  const int64_t nblocks = (g.N + 15) / 16;
+  const int64_t nblocks = (g.N + SdCfg<WIDE>::RPS - 1) / SdCfg<WIDE>::RPS;
   const unsigned nwg = (unsigned)(nblocks < ncu ? nblocks : ncu);   // one persistent workgroup per CU
   hipLaunchKernelGGL(kern, dim3(nwg), dim3(SK_NT), SD_SMEM + SD_RED, s, (int)g.M, (int)g.N, (int)g.K,
                      g.A, g.lda, g.B, g.ldb, g.C, g.ldc);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
-template <typename Tag>
+template <typename Tag, bool WIDE>
 int run_skinny_dma_t(const GemmArgs& g, hipStream_t s) {
   switch ((g.M + 15) / 16) {
-    case 1: return launch_skinny_dma<Tag, 1>(g, s);
-    case 2: return launch_skinny_dma<Tag, 2>(g, s);
-    case 3: return launch_skinny_dma<Tag, 3>(g, s);
-    case 4: return launch_skinny_dma<Tag, 4>(g, s);
+    case 1: return launch_skinny_dma<Tag, 1, WIDE>(g, s);
+    case 2: return launch_skinny_dma<Tag, 2, WIDE>(g, s);
+    case 3: return launch_skinny_dma<Tag, 3, WIDE>(g, s);
+    case 4: return launch_skinny_dma<Tag, 4, WIDE>(g, s);
   }
   return MLT_ERR_UNSUPPORTED;
 }
@@ -371,13 +396,15 @@ int run_gemm_skinny(const GemmArgs& g, hipStream_t s) {
   return g.dtype == MLT_BF16 ? run_skinny_t<bf16_tag>(g, s) : run_skinny_t<f16_tag>(g, s);
 }
 
-// The streaming variant addresses B rows with 32-bit byte offsets from the workgroup's first row.
+// The streaming variant addresses B rows with 32-bit byte offsets from the column block's first row.
 bool gemm_skinny_dma_ok(const GemmArgs& g) {
-  return gemm_skinny_ok(g) && g.ldb * 2 * 16 + g.K * 2 < ((int64_t)1 << 32);
+  return gemm_skinny_ok(g) && g.ldb * 2 * 64 + g.K * 2 < ((int64_t)1 << 32);
 }
 
-int run_gemm_skinny_dma(const GemmArgs& g, hipStream_t s) {
-  return g.dtype == MLT_BF16 ? run_skinny_dma_t<bf16_tag>(g, s) : run_skinny_dma_t<f16_tag>(g, s);
+int run_gemm_skinny_dma(const GemmArgs& g, bool wide, hipStream_t s) {
+  if (wide)
+    return g.dtype == MLT_BF16 ? run_skinny_dma_t<bf16_tag, true>(g, s) : run_skinny_dma_t<f16_tag, true>(g, s);
+  return g.dtype == MLT_BF16 ? run_skinny_dma_t<bf16_tag, false>(g, s) : run_skinny_dma_t<f16_tag, false>(g, s);
 }
 
 }  // namespace mlt

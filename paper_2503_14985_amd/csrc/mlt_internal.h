@@ -14,7 +14,8 @@ enum GemmVariant {
   GEMM_256_W8T = 5,   // 256x256x64, 8 wavefronts (4x2) of 64x128
   GEMM_256_PP = 6,    // 256x256x64, 8 wavefronts (2x4), two-group schedule, direct-to-LDS loads
   GEMM_SKINNY = 7,    // M <= 64, B stored N x K: 16 columns per workgroup, K split over 8 wavefronts
-  GEMM_SKINNY_DMA = 8,  // same shapes, B streamed through an LDS ring in 1 KB row pieces
+  GEMM_SKINNY_DMA = 8,  // same shapes, B streamed through an LDS ring: 16 columns x 512 k per stage
+  GEMM_SKINNY_DMAW = 9, // the same with 64 columns x 128 k per stage
   GEMM_NUM_VARIANTS
 };
 
@@ -42,7 +43,7 @@ int run_gemm_pp(const GemmArgs& g, hipStream_t s);
 bool gemm_skinny_ok(const GemmArgs& g);        // gemm_skinny.hip
 int run_gemm_skinny(const GemmArgs& g, hipStream_t s);
 bool gemm_skinny_dma_ok(const GemmArgs& g);
-int run_gemm_skinny_dma(const GemmArgs& g, hipStream_t s);
+int run_gemm_skinny_dma(const GemmArgs& g, bool wide, hipStream_t s);
 
 struct MhaArgs {
   int64_t B, H, Sq, Sk, D;

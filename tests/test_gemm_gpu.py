@@ -79,22 +79,27 @@ def test_skinny_kernel(shape, dtype):
 
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("shape", [(16, 1024, 512), (1, 1031, 520), (17, 2048, 4096 + 8), (64, 1040, 1024),
-                                   (33, 4096, 8), (48, 1500, 7000), (16, 16 * 300 + 5, 1536)])
-def test_skinny_streaming_kernel(shape, dtype):
-    # B streamed through the LDS ring by persistent workgroups: one to four 16-row tiles of A,
-    # ragged N (clamped rows), K below / equal to / not a multiple of the 512-wide stage, a single
-    # 8-wide K, and more column blocks than CUs (several blocks per workgroup)
+                                   (33, 4096, 8), (48, 1500, 7000), (16, 16 * 300 + 5, 1536),
+                                   (20, 64 * 300 + 21, 1160)])
+@pytest.mark.parametrize("form", ["skinnydma", "skinnydmaw"])
+def test_skinny_streaming_kernel(shape, dtype, form):
+    # B streamed through the LDS ring by persistent workgroups, in both stage shapes (16 columns x
+    # 512 k, 64 columns x 128 k): one to four 16-row tiles of A, ragged N (clamped rows), K below /
+    # equal to / not a multiple of the stage, a single 8-wide K, and more column blocks than CUs
+    # (several blocks per workgroup, the ring wrapping across block ends)
     M, N, K = shape
-    name, _ = _go(M, N, K, dtype, True, std=0.02, seed=8, variant="skinnydma")
-    assert name.endswith("_stream")
+    name, _ = _go(M, N, K, dtype, True, std=0.02, seed=8, variant=form)
+    assert name.endswith("cols_stream")
 
 
 def test_skinny_streaming_kernel_is_the_default_for_large_b():
     # M <= 16 and B of 2^25 elements: routed to the streaming kernel without any override
     name, _ = _go(16, 8192, 4096, BF16, True, std=0.02, seed=9)
     assert name.endswith("_stream")
-    name, _ = _go(17, 8192, 4096, BF16, True, std=0.02, seed=9)
+    name, _ = _go(17, 8192, 4096, BF16, True, std=0.02, seed=9)       # taller A, too few 64-column blocks
     assert "skinny" in name and not name.endswith("_stream")
+    name, _ = _go(40, 16384, 2048, FP16, True, std=0.02, seed=9)      # taller A: the 64-column form
+    assert name == "gemm_nt_skinny_64cols_stream"
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (37, 53, 29), (65, 63, 33), (16, 8, 8), (8, 16, 24),
