@@ -67,6 +67,22 @@ int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
                  int64_t ldb, int transB, float* C, int64_t ldc, int dtype, void* stream);
 
 /*
+ * GEMM with a fused epilogue, C = act(A*B + bias): the post-operation fusion the paper expects to
+ * fall out of its layout propagation from the root operation (Section 3.1, the remark on pre- and
+ * post-operation fusion), here written into the kernels' epilogues. Arguments as for mlt_gemm,
+ * plus
+ *   bias   device, N elements of `dtype` added to every row of A*B in fp32 before the activation,
+ *          or NULL for none; only read
+ *   act    0 none, 1 ReLU max(x, 0), 2 GELU in its exact form x * Phi(x) = x/2 * (1 + erf(x/sqrt 2))
+ * The fp32 accumulator plus bias goes through the activation in fp32 and is rounded once (RNE) to
+ * the 16-bit C. K = 0 gives C = act(bias) (act(0) without a bias). Returns as mlt_gemm;
+ * MLT_ERR_INVALID_ARG also for an unknown `act` or a misaligned bias.
+ */
+int mlt_gemm_bias_act(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                      int64_t ldb, int transB, const void* bias, int act, void* C, int64_t ldc,
+                      int dtype, void* stream);
+
+/*
  * Attention forward, Section 2.5 / Algorithm 1 of the paper, per batch b and head h:
  *   O = softmax(scale * Q K^T  [+ causal mask]) V
  * computed tile by tile with the online-softmax recurrence (running row maximum m and row sum

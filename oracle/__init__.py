@@ -53,6 +53,8 @@ def _bind(path: str):
     lib.oracle_gemm_sampled.restype = i32
     lib.oracle_gemm_sampled.argtypes = [i64, i64, i64, p, i64, p, i64, i32, i64, p, p, p, p,
                                         i32, i32]
+    lib.oracle_gemm_epilogue.restype = i32
+    lib.oracle_gemm_epilogue.argtypes = [i64, i64, p, i64, p, p, i32, i32]
     lib.oracle_mha_fwd.restype = i32
     lib.oracle_mha_fwd.argtypes = [i64, i64, i64, i64, i64, p, p, p, p, dbl, i32, i32, i32]
     lib.oracle_mha_fwd_rows.restype = i32
@@ -146,6 +148,26 @@ def gemm(A: np.ndarray, B: np.ndarray, dtype: int, transB: bool = False, nthread
                              dtype, nthreads)
     if rc != 0:
         raise RuntimeError("oracle_gemm failed: %d" % rc)
+    return C, T
+
+
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+
+
+def gemm_bias_act(A, B, bias, act: int, dtype: int, transB: bool = False, nthreads: int = 0):
+    """(Y_ref, T) for the fused GEMM Y = act(A*B + bias): the exact product from `gemm`, then the
+    epilogue in fp64. bias is a uint16 [N] array in `dtype` or None; T = |A||B| + |bias|."""
+    C, T = gemm(A, B, dtype, transB=transB, nthreads=nthreads)
+    M, N = C.shape
+    if bias is not None:
+        _u16(bias)
+        if bias.shape != (N,):
+            raise ValueError("bias must have N elements")
+        bias = np.ascontiguousarray(bias)
+    rc = _load().oracle_gemm_epilogue(M, N, _ptr(C), N, _ptr(T), _ptr(bias) if bias is not None else None,
+                                      int(act), dtype)
+    if rc != 0:
+        raise RuntimeError("oracle_gemm_epilogue failed: %d" % rc)
     return C, T
 
 

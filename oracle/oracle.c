@@ -171,6 +171,34 @@ int oracle_gemm_sampled(int64_t M, int64_t N, int64_t K, const uint16_t* A, int6
   return 0;
 }
 
+/*
+ * Epilogue of the fused GEMM (the post-operation fusion remark of Section 3.1): applied in place
+ * to exact products x = (A*B)[i][j] held in fp64, row-major with row stride ldx,
+ *   y = act(x + bias[j]),   bias one value per COLUMN in the 16-bit input type (or none),
+ *   act 0: identity, 1: ReLU max(y, 0), 2: GELU in its exact form y * Phi(y) with the standard
+ *   normal distribution function Phi(y) = (1 + erf(y / sqrt 2)) / 2.
+ * mag, if given, holds the magnitude sums |A||B| and receives + |bias[j]| (the scale the parity
+ * tolerance is relative to).
+ */
+int oracle_gemm_epilogue(int64_t M, int64_t N, double* X, int64_t ldx, double* mag,
+                         const uint16_t* bias, int act, int dtype) {
+  if (M < 0 || N < 0 || act < 0 || act > 2 || (dtype != 0 && dtype != 1)) return -1;
+  for (int64_t i = 0; i < M; ++i) {
+    for (int64_t j = 0; j < N; ++j) {
+      double y = X[i * ldx + j];
+      if (bias) {
+        const double bj = widen(bias[j], dtype);
+        y += bj;
+        if (mag) mag[i * ldx + j] += fabs(bj);
+      }
+      if (act == 1) y = y > 0.0 ? y : 0.0;
+      if (act == 2) y = 0.5 * y * (1.0 + erf(y / sqrt(2.0)));
+      X[i * ldx + j] = y;
+    }
+  }
+  return 0;
+}
+
 /* ------------------------------------------------------------------------------- attention */
 
 /*

@@ -77,7 +77,7 @@ template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
-    int nbn, int acc32) {
+    int nbn, int epi, const uint16_t* __restrict__ bias) {
   typedef GemmTile<Tag, BM, BN, BK, WM, WN, TRANSB> Cfg;
   typedef typename Elem<Tag>::vec8 V8;
   extern __shared__ __align__(16) char smem[];
@@ -283,17 +283,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
   // ---- epilogue: fp32 -> 16-bit (RNE), guarded element stores
   const int row_base = m0 + wm * (BM / WM) + 4 * (lane >> 5);
   const int col_base = n0 + wn * (BN / WN) + (lane & 31);
+  gemm_epilogue<Tag>([&](auto&& out) {
 #pragma unroll
-  for (int i = 0; i < Cfg::TM; ++i)
+    for (int i = 0; i < Cfg::TM; ++i)
 #pragma unroll
-    for (int j = 0; j < Cfg::TN; ++j) {
-      const int col = col_base + j * 32;
+      for (int j = 0; j < Cfg::TN; ++j) {
+        const int col = col_base + j * 32;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (row < M && col < N) store_c<Tag>(C, (int64_t)row * ldc + col, acc[i][j][r], acc32);
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < M && col < N) out((int64_t)row * ldc + col, col, acc[i][j][r]);
+        }
       }
-    }
+  }, C, epi, bias);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -304,7 +306,7 @@ template <typename Tag>
 __global__ __launch_bounds__(256) void gemm_general_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, int transB, uint16_t* __restrict__ C,
-    int64_t ldc, int acc32) {
+    int64_t ldc, int epi, const uint16_t* __restrict__ bias) {
   typedef typename Elem<Tag>::vec8 V8;
   constexpr int BM = 64, BN = 64, BK = 32, LDS_S = BK + 8;
   __shared__ __align__(16) uint16_t As[BM * LDS_S];
@@ -345,11 +347,13 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
     __syncthreads();
   }
   const int col = n0 + wn * 32 + (lane & 31);
+  gemm_epilogue<Tag>([&](auto&& out) {
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int row = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    if (row < M && col < N) store_c<Tag>(C, (int64_t)row * ldc + col, acc[r], acc32);
-  }
+    for (int r = 0; r < 16; ++r) {
+      const int row = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (row < M && col < N) out((int64_t)row * ldc + col, col, acc[r]);
+    }
+  }, C, epi, bias);
 }
 
 // K == 0: the empty sum (only launched when C is overwritten; C += 0 is a no-op).
@@ -378,7 +382,7 @@ static int launch_tile(const GemmArgs& g, hipStream_t s) {
   }
   const int nbm = (int)((g.M + BM - 1) / BM), nbn = (int)((g.N + BN - 1) / BN);
   hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(Cfg::NT), Cfg::SMEM, s, (int)g.M, (int)g.N,
-                     (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.acc32);
+                     (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.epi(), g.bias);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
@@ -386,7 +390,7 @@ template <typename Tag>
 static int launch_general(const GemmArgs& g, hipStream_t s) {
   dim3 grid((unsigned)((g.N + 63) / 64), (unsigned)((g.M + 63) / 64));
   hipLaunchKernelGGL(gemm_general_kernel<Tag>, grid, dim3(256), 0, s, (int)g.M, (int)g.N, (int)g.K,
-                     g.A, g.lda, g.B, g.ldb, g.transB, g.C, g.ldc, g.acc32);
+                     g.A, g.lda, g.B, g.ldb, g.transB, g.C, g.ldc, g.epi(), g.bias);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
@@ -400,8 +404,10 @@ static bool fast_path_ok(const GemmArgs& g) {
 
 GemmPlan plan_gemm(const GemmArgs& g) {
   GemmPlan p;
-  if (g.K == 0) { p.variant = GEMM_ZERO; p.name = "gemm_zero"; return p; }
-  if (!fast_path_ok(g) || g.forced == GEMM_GENERAL) {
+  // K == 0: the empty sum; with a fused epilogue C = act(bias), which the general kernel's epilogue
+  // computes after zero K steps
+  if (g.K == 0 && !g.fused()) { p.variant = GEMM_ZERO; p.name = "gemm_zero"; return p; }
+  if (g.K == 0 || !fast_path_ok(g) || g.forced == GEMM_GENERAL) {
     p.variant = GEMM_GENERAL; p.name = "gemm_general_64x64x32";
     p.bm = 64; p.bn = 64; p.bk = 32; p.wm = 2; p.wn = 2;
     return p;

@@ -88,7 +88,7 @@ template <typename Tag, bool TRANSB>
 __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
-    int nbn, int acc32) {
+    int nbn, int epi, const uint16_t* __restrict__ bias) {
   typedef typename Elem<Tag>::vec8 V8;
   extern __shared__ __align__(16) char smem[];
 
@@ -260,17 +260,19 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   // ---- epilogue: fp32 -> 16-bit (RNE) and store, or add to the fp32 C; guarded per element
   const int row_base = m0 + wm * 128 + 4 * h;
   const int col_base = n0 + wn * 64 + lq;
+  gemm_epilogue<Tag>([&](auto&& out) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = col_base + j * 32;
+      for (int j = 0; j < 2; ++j) {
+        const int col = col_base + j * 32;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-        if (row < M && col < N) store_c<Tag>(C, (int64_t)row * ldc + col, acc[i][j][r], acc32);
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
+          if (row < M && col < N) out((int64_t)row * ldc + col, col, acc[i][j][r]);
+        }
       }
-    }
+  }, C, epi, bias);
 }
 
 bool gemm_pp_ok(const GemmArgs& g) {
@@ -300,7 +302,7 @@ static int launch_pp(const GemmArgs& g, hipStream_t s) {
   }
   const int nbm = (int)((g.M + PP_BM - 1) / PP_BM), nbn = (int)((g.N + PP_BN - 1) / PP_BN);
   hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(PP_NT), PP_SMEM, s, (int)g.M, (int)g.N, (int)g.K,
-                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.acc32);
+                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.epi(), g.bias);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 

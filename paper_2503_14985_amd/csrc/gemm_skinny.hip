@@ -386,7 +386,7 @@ int run_skinny_dma_t(const GemmArgs& g, hipStream_t s) {
 // Worth it only when the columns alone fill the chip (one workgroup per 16 columns).
 bool gemm_skinny_ok(const GemmArgs& g) {
   auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-  if (!g.transB || g.acc32 || g.M > 16 * SK_MAXMT || g.N < 1024) return false;
+  if (!g.transB || g.acc32 || g.fused() || g.M > 16 * SK_MAXMT || g.N < 1024) return false;
   if (!al16(g.A) || !al16(g.B)) return false;
   if (g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
   return true;

@@ -121,6 +121,29 @@ int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
   return rc;
 }
 
+int mlt_gemm_bias_act(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                      int64_t ldb, int transB, const void* bias, int act, void* C, int64_t ldc,
+                      int dtype, void* stream) {
+  int rc = check_gemm(M, N, K, A, lda, B, ldb, transB, C, ldc, dtype);
+  if (rc != MLT_OK) return rc;
+  if (act < 0 || act > 2) return MLT_ERR_INVALID_ARG;
+  if (bias && (reinterpret_cast<uintptr_t>(bias) & 1)) return MLT_ERR_INVALID_ARG;
+  if (M == 0 || N == 0) return MLT_OK;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
+             (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 0};
+  g.bias = (const uint16_t*)bias;
+  g.act = act;
+  GemmPlan p = plan_gemm(g);
+  hipStream_t s = (hipStream_t)stream;
+  {
+    TimedRegion t(s);
+    rc = run_gemm(g, p, s);
+  }
+  if (rc == MLT_OK) g_last_kernel = p.name;
+  return rc;
+}
+
 int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const void* Q,
                 const void* K, const void* V, void* O, float scale, int causal, int dtype,
                 void* stream) {

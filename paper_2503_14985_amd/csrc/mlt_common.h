@@ -86,6 +86,31 @@ __device__ __forceinline__ void store_c(uint16_t* C, int64_t idx, float v, int a
   else C[idx] = Elem<Tag>::from_f32(v);
 }
 
+// Epilogue word of the GEMM kernels: bit 0 = add into an fp32 C (no bias, no activation);
+// otherwise bits 1..2 = activation applied to acc + bias[col] before rounding to the 16-bit C.
+enum { EPI_ACC32 = 1, EPI_ACT_SHIFT = 1, ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
+__device__ __forceinline__ float epi_act(float v, int act) {
+  if (act == ACT_RELU) return v > 0.f ? v : 0.f;
+  if (act == ACT_GELU) return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));   // v * Phi(v)
+  return v;
+}
+// The three ways a kernel's result elements leave: `each(fn)` calls fn(index into C, column, value)
+// for every element this lane owns that lies inside the matrix.
+template <typename Tag, typename Each>
+__device__ __forceinline__ void gemm_epilogue(Each&& each, uint16_t* C, int epi, const uint16_t* bias) {
+  if (epi & EPI_ACC32) {
+    each([&](int64_t idx, int, float v) { reinterpret_cast<float*>(C)[idx] += v; });
+  } else if (epi == 0 && bias == nullptr) {
+    each([&](int64_t idx, int, float v) { C[idx] = Elem<Tag>::from_f32(v); });
+  } else {
+    const int act = epi >> EPI_ACT_SHIFT;
+    each([&](int64_t idx, int col, float v) {
+      if (bias) v += Elem<Tag>::to_f32(bias[col]);
+      C[idx] = Elem<Tag>::from_f32(epi_act(v, act));
+    });
+  }
+}
+
 // D(32x32) += A(32x16) * B(16x32). Lane l supplies A[l%32][8*(l/32) .. +7] and
 // B[8*(l/32) .. +7][l%32]; it owns D[8*(r/4) + 4*(l/32) + r%4][l%32] in register r (0..15).
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {

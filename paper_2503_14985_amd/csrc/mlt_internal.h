@@ -27,6 +27,10 @@ struct GemmArgs {
   int dtype;
   int forced;  // GemmVariant or GEMM_AUTO
   int acc32;   // 0: C is 16-bit and overwritten; 1: C is fp32 and accumulated into (C += A*B)
+  const uint16_t* bias = nullptr;  // N elements of the input type added to every row (16-bit C only), or null
+  int act = 0;                     // 0 none, 1 relu, 2 gelu: applied after the bias (16-bit C only)
+  int epi() const { return acc32 ? 1 : (act << 1); }   // the kernels' epilogue word
+  bool fused() const { return bias != nullptr || act != 0; }
 };
 
 struct GemmPlan {

@@ -72,6 +72,12 @@ def gemm_inputs(M: int, N: int, K: int, dtype: int, seed: int, dist: str = "norm
     return pad(a, lda), pad(b, ldb)
 
 
+def bias_input(N: int, dtype: int, seed: int, std: float = 1.0) -> np.ndarray:
+    """A bias vector of N values ~ N(0, std^2) as uint16 patterns (for the fused GEMM epilogue)."""
+    rng = np.random.default_rng(seed + 7919)
+    return to_bits(_draw(rng, (N,), "normal", std), dtype)
+
+
 def mha_inputs(B: int, H: int, Sq: int, Sk: int, D: int, dtype: int, seed: int,
                q_gain: float = 1.0):
     """Q [B,H,Sq,D], K and V [B,H,Sk,D], i.i.d. N(0,1) (Q multiplied by q_gain), uint16 patterns."""

@@ -91,6 +91,35 @@ def run_gemm(A, B, dtype, transB=False, device="cuda:0", lda=None, ldb=None, ldc
     return out
 
 
+# Fused epilogue: y = act(x + bias). The activation has Lipschitz constant 1 (none, ReLU) or
+# max |gelu'| = 1.129 (GELU), so an error e in x + bias becomes at most 1.13 * e; the final rounding to
+# 16 bit is relative to |y| <= |x + bias| <= T + |bias|, which the GEMM tolerance (four rounding units
+# of the output type) covers as it does for the plain GEMM.
+ACT_LIPSCHITZ = {0: 1.0, 1: 1.0, 2: 1.13}
+
+
+def run_check_gemm_bias_act(A, B, bias, act, dtype, transB=False, device="cuda:0"):
+    from paper_2503_14985_amd import binding
+    dev = torch.device(device)
+    tA = inputs.bits_to_torch(np.ascontiguousarray(A), dtype, dev)
+    tB = inputs.bits_to_torch(np.ascontiguousarray(B), dtype, dev)
+    tb = inputs.bits_to_torch(bias, dtype, dev) if bias is not None else None
+    M = A.shape[0]
+    N = B.shape[0] if transB else B.shape[1]
+    buf = torch.full((M, N + 3), float("nan"), dtype=tA.dtype, device=dev)
+    out = binding.mlt_gemm_bias_act(tA, tB, tb, act, C=buf[:, :N], transB=transB)
+    torch.cuda.synchronize()
+    assert torch.isnan(buf[:, N:]).all(), "kernel wrote into the padding of C"
+    Yg = out.detach().cpu().double().numpy()
+    Yref, T = oracle.gemm_bias_act(A, B, bias, act, dtype, transB=transB)
+    err = np.abs(Yg - Yref)
+    bound = ACT_LIPSCHITZ[act] * GEMM_TOL[dtype] * T + 1e-6
+    worst = float(np.max(err / bound)) if err.size else 0.0
+    assert np.all(np.isfinite(Yg)), "non-finite output"
+    assert np.all(err <= bound), "fused GEMM parity: worst err/bound = %.3f, max err %.3g" % (worst, err.max())
+    return {"max_err": float(err.max()) if err.size else 0.0, "worst_ratio": worst, "n": int(err.size)}
+
+
 def mha_sample_rows(B, H, Sq, rng, n_bh=8, n_rows=512, tile=128):
     bh = {(0, 0), (B - 1, H - 1)}
     while len(bh) < min(n_bh, B * H):

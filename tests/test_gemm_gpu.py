@@ -215,3 +215,53 @@ def test_accumulate_edge_cases():
     assert "skinny" not in binding.mlt_last_kernel() and torch.all(C == 64.0)
     with pytest.raises(ValueError):
         binding.mlt_gemm_acc(A, B, torch.zeros((4, 2048), dtype=torch.bfloat16, device=dev), transB=True)
+
+
+@pytest.mark.parametrize("act", [0, 1, 2])
+@pytest.mark.parametrize("with_bias", [False, True])
+@pytest.mark.parametrize("variant,shape", [("256pp", (520, 776, 320)), ("256", (300, 264, 200)),
+                                           ("128", (260, 392, 136)), ("general", (70, 53, 29)),
+                                           (None, (16, 2048, 512))])
+def test_fused_bias_activation(variant, shape, with_bias, act):
+    """C = act(A*B + bias) through every kernel family's epilogue (several tiles, ragged edges);
+    the last shape would take the skinny kernel, which has no fused epilogue, and must not."""
+    from paper_2503_14985_amd import binding
+    M, N, K = shape
+    for dtype, transB in ((BF16, False), (FP16, True)):
+        A, B = inputs.gemm_inputs(M, N, K, dtype, 11, transB=transB)
+        bias = inputs.bias_input(N, dtype, 11, std=4.0) if with_bias else None
+        if variant:
+            os.environ["MLT_GEMM_VARIANT"] = variant
+        st = pu.run_check_gemm_bias_act(A, B, bias, act, dtype, transB=transB)
+        name = binding.mlt_last_kernel()
+        print("   kernel=%s %s" % (name, st), flush=True)
+        if with_bias or act:
+            assert "skinny" not in name
+        if variant == "256pp":
+            assert name.endswith("_pp")
+
+
+def test_fused_epilogue_edge_cases():
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    # K = 0: C = act(bias)
+    bias = torch.tensor([-2.0, 0.0, 3.0, -0.5, 1.5], dtype=torch.bfloat16, device=dev)
+    A = torch.empty((4, 0), dtype=torch.bfloat16, device=dev)
+    B = torch.empty((0, 5), dtype=torch.bfloat16, device=dev)
+    C = binding.mlt_gemm_bias_act(A, B, bias, binding.ACT_RELU)
+    torch.cuda.synchronize()
+    assert torch.equal(C, torch.relu(bias).expand(4, 5))
+    C = binding.mlt_gemm_bias_act(A, B, None, binding.ACT_GELU)
+    torch.cuda.synchronize()
+    assert torch.all(C == 0)
+    # without bias and activation it is mlt_gemm, bit for bit
+    A = torch.randn(300, 200, dtype=torch.float16, device=dev)
+    B = torch.randn(200, 264, dtype=torch.float16, device=dev)
+    assert torch.equal(binding.mlt_gemm_bias_act(A, B), binding.mlt_gemm(A, B))
+    # errors: unknown activation, bias of the wrong length / dtype
+    with pytest.raises(binding.MltError):
+        binding.mlt_gemm_bias_act(A, B, None, 3)
+    with pytest.raises(ValueError):
+        binding.mlt_gemm_bias_act(A, B, torch.zeros(263, dtype=torch.float16, device=dev))
+    with pytest.raises(ValueError):
+        binding.mlt_gemm_bias_act(A, B, torch.zeros(264, dtype=torch.bfloat16, device=dev))

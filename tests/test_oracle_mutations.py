@@ -36,6 +36,13 @@ MUTATIONS = [
     ("paged: head stride dropped for K", "Kc + ((pb * H + h) * block_size", "Kc + ((pb * H) * block_size"),
     ("paged: scale dropped", "s[p] = scale * dot;", "s[p] = dot;"),
     ("paged: weights not normalised", "const double wp = s[p] / l;", "const double wp = s[p];"),
+    ("epilogue: bias taken by row", "const double bj = widen(bias[j], dtype);",
+     "const double bj = widen(bias[i], dtype);"),
+    ("epilogue: bias subtracted", "y += bj;", "y -= bj;"),
+    ("epilogue: magnitude ignores the bias", "mag[i * ldx + j] += fabs(bj);", "mag[i * ldx + j] += 0.0;"),
+    ("epilogue: relu keeps the negative side", "y = y > 0.0 ? y : 0.0;", "y = y < 0.0 ? y : 0.0;"),
+    ("epilogue: gelu argument not divided by sqrt 2", "erf(y / sqrt(2.0))", "erf(y)"),
+    ("epilogue: gelu without the one half", "y = 0.5 * y * (1.0 +", "y = y * (1.0 +"),
     ("gemm: B read transposed", "transB ? B[j * ldb + k] : B[k * ldb + j]",
      "transB ? B[k * ldb + j] : B[j * ldb + k]"),
     ("gemm: last k dropped", "for (int64_t k = 0; k < K; ++k) {\n    double a = widen(A[i",

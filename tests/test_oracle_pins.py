@@ -238,6 +238,81 @@ def test_gemm_edge_k0_and_single():
     assert C[0, 0] == -1.5
 
 
+# ---------------------------------------------------------------------------- fused epilogue
+
+def test_epilogue_without_bias_and_activation_is_the_gemm():
+    A, B = inputs.gemm_inputs(5, 7, 9, BF16, seed=21)
+    C, T = oracle.gemm(A, B, BF16)
+    Y, Ty = oracle.gemm_bias_act(A, B, None, oracle.ACT_NONE, BF16)
+    assert np.array_equal(Y, C) and np.array_equal(Ty, T)
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+def test_epilogue_bias_is_per_column_added_before_the_activation(dtype):
+    # A = 0: the product vanishes and every ROW of the result is act(bias); 3 x 4, so a bias taken
+    # by row, a subtracted bias or an activation applied before the bias all show
+    A = np.zeros((3, 2), dtype=np.uint16)
+    B = bits(np.ones((2, 4), dtype=np.float32), dtype)
+    b = np.array([-1.0, 0.5, 2.0, -3.0])
+    bias = bits(b.astype(np.float32), dtype)
+    Y, T = oracle.gemm_bias_act(A, B, bias, oracle.ACT_NONE, dtype)
+    assert np.array_equal(Y, np.tile(b, (3, 1)))
+    assert np.array_equal(T, np.tile(np.abs(b), (3, 1)))          # the magnitude includes |bias|
+    Y, _ = oracle.gemm_bias_act(A, B, bias, oracle.ACT_RELU, dtype)
+    assert np.array_equal(Y, np.tile(np.maximum(b, 0.0), (3, 1)))
+
+
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+def test_epilogue_integer_brute_force(dtype):
+    rng = np.random.default_rng(22)
+    a, b = small_ints(rng, (4, 6)), small_ints(rng, (6, 5))
+    bias = small_ints(rng, (5,), -20, 20)
+    want = [[sum(int(a[i, k]) * int(b[k, j]) for k in range(6)) + int(bias[j]) for j in range(5)]
+            for i in range(4)]
+    Y, _ = oracle.gemm_bias_act(bits(a, dtype), bits(b, dtype), bits(bias, dtype), oracle.ACT_NONE, dtype)
+    assert np.array_equal(Y, np.array(want, dtype=np.float64))
+    Y, _ = oracle.gemm_bias_act(bits(a, dtype), bits(b, dtype), bits(bias, dtype), oracle.ACT_RELU, dtype)
+    assert np.array_equal(Y, np.maximum(np.array(want, dtype=np.float64), 0.0))
+    Yt, _ = oracle.gemm_bias_act(bits(a, dtype), bits(b.T.copy(), dtype), bits(bias, dtype),
+                                 oracle.ACT_RELU, dtype, transB=True)
+    assert np.array_equal(Yt, Y)
+
+
+def test_epilogue_gelu_against_the_normal_table_and_erfc():
+    # x reaches the epilogue exactly as the 1 x 1 product 1 * x (+ bias 0 or with x split as
+    # (x - 1) + bias 1)
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "gelu_phi_table.txt"))
+            if l.strip() and not l.startswith("#")]
+    one = bits([[1.0]], FP16)
+    for xs, phis in rows:
+        x, phi = float(xs), float(phis)
+        for sign in (1.0, -1.0):
+            xv = sign * x
+            ph = phi if sign > 0 else 1.0 - phi                   # Phi(-x) = 1 - Phi(x)
+            Y, _ = oracle.gemm_bias_act(one, bits([[xv]], FP16), None, oracle.ACT_GELU, FP16)
+            assert abs(Y[0, 0] - xv * ph) <= 4e-15 * max(1.0, abs(xv)), (xv, Y[0, 0])
+            # the same value through the complementary error function (another libm routine)
+            assert abs(Y[0, 0] - 0.5 * xv * math.erfc(-xv / math.sqrt(2.0))) <= 1e-15 * max(1.0, abs(xv))
+            Y2, _ = oracle.gemm_bias_act(one, bits([[xv - 1.0]], FP16), bits([1.0], FP16),
+                                         oracle.ACT_GELU, FP16)
+            assert Y2[0, 0] == Y[0, 0]
+    # far out: gelu(x) -> x and gelu(-x) -> -0
+    Y, _ = oracle.gemm_bias_act(one, bits([[16.0]], FP16), None, oracle.ACT_GELU, FP16)
+    assert Y[0, 0] == 16.0
+    Y, _ = oracle.gemm_bias_act(one, bits([[-16.0]], FP16), None, oracle.ACT_GELU, FP16)
+    assert abs(Y[0, 0]) < 1e-50
+
+
+@pytest.mark.parametrize("act", [0, 1, 2])
+def test_epilogue_vs_torch_float64_composition(act):
+    A, B = inputs.gemm_inputs(9, 11, 33, BF16, seed=23)
+    bias = inputs.to_bits(np.random.default_rng(24).standard_normal(11).astype(np.float32), BF16)
+    Y, _ = oracle.gemm_bias_act(A, B, bias, act, BF16)
+    x = torch.from_numpy(f64(A, BF16)) @ torch.from_numpy(f64(B, BF16)) + torch.from_numpy(f64(bias, BF16))
+    want = [x, torch.relu(x), torch.nn.functional.gelu(x)][act].numpy()
+    assert np.max(np.abs(Y - want)) <= 1e-13
+
+
 # -------------------------------------------------------------------------------- attention
 
 def torch_attention(q, k, v, scale, causal):
