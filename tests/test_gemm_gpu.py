@@ -61,6 +61,18 @@ def test_two_group_kernel(shape, transB, dtype):
     assert name.endswith("_pp")
 
 
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+@pytest.mark.parametrize("shape", [(520, 776, 320), (512, 768, 256), (100, 40, 64), (257, 264, 128),
+                                   (300, 520, 64 * 7)])
+def test_four_wavefront_pipelined_kernel(shape, transB, dtype):
+    # 2 x 2 wavefronts of 128 x 128 with the hand-pipelined K loop: one, two, three and more K steps
+    # (the loop issues loads and prefetches past the last step into dead slots), ragged M/N
+    M, N, K = shape
+    name, _ = _go(M, N, K, dtype, transB, variant="256w4", seed=12)
+    assert name.endswith("_swp")
+
+
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("shape", [(16, 1024, 4096), (1, 1040, 512), (7, 1500, 264), (33, 2048, 8200),
                                    (64, 1024, 1000), (48, 1031, 4096 + 32),
