@@ -436,11 +436,11 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   }
   // Big tile when it still fills the chip, otherwise the small one.
   const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-  int v = tiles256 >= 192 ? (gemm_pp_ok(g) ? GEMM_256_PP : GEMM_256_W8) : GEMM_128;
+  int v = tiles256 >= 192 ? (gemm_pp_ok(g) ? GEMM_256_PP16 : GEMM_256_W8) : GEMM_128;
   if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS && g.forced != GEMM_SKINNY &&
       g.forced != GEMM_SKINNY_DMA && g.forced != GEMM_SKINNY_DMAW)
     v = g.forced;
-  if ((v == GEMM_256_PP || v == GEMM_256_W4) && !gemm_pp_ok(g)) v = GEMM_256_W8;
+  if ((v == GEMM_256_PP || v == GEMM_256_PP16 || v == GEMM_256_W4) && !gemm_pp_ok(g)) v = GEMM_256_W8;
   p.variant = v;
   p.bk = 64;
   switch (v) {
@@ -452,6 +452,9 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       p.name = g.transB ? "gemm_nt_256x256x64_w4x2" : "gemm_nn_256x256x64_w4x2"; break;
     case GEMM_256_PP: p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x4_pp" : "gemm_nn_256x256x64_w2x4_pp"; break;
+    case GEMM_256_PP16: p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
+      p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
+      p.name = g.transB ? "gemm_nt_256x256x64_w2x4_pp16" : "gemm_nn_256x256x64_w2x4_pp16"; break;
     case GEMM_256_W4: p.bm = p.bn = 256; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x2_swp" : "gemm_nn_256x256x64_w2x2_swp"; break;
     default: p.bm = p.bn = 128; p.wm = 2; p.wn = 2;
@@ -481,7 +484,8 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_256_W8: return launch_tile_tb<Tag, 256, 256, 64, 2, 4>(g, s);
     case GEMM_256_W8T: return launch_tile_tb<Tag, 256, 256, 64, 4, 2>(g, s);
     case GEMM_128: return launch_tile_tb<Tag, 128, 128, 64, 2, 2>(g, s);
-    case GEMM_256_PP: return run_gemm_pp(g, s);
+    case GEMM_256_PP: return run_gemm_pp(g, 32, s);
+    case GEMM_256_PP16: return run_gemm_pp(g, 16, s);
     case GEMM_256_W4: return run_gemm_w4(g, s);
     case GEMM_SKINNY: return run_gemm_skinny(g, s);
     case GEMM_SKINNY_DMA: return run_gemm_skinny_dma(g, false, s);

@@ -29,7 +29,7 @@ bool device_is_gfx950() {
 }
 
 int forced_gemm_variant() {
-  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 256w8 | 256w8t | 256pp | 256w4 | skinny | skinnydma | skinnydmaw.
+  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 256w8 | 256w8t | 256pp | 256pp16 | 256w4 | skinny | skinnydma | skinnydmaw.
   const char* e = getenv("MLT_GEMM_VARIANT");
   if (!e || !*e) return GEMM_AUTO;
   if (!strcmp(e, "general")) return GEMM_GENERAL;
@@ -39,6 +39,7 @@ int forced_gemm_variant() {
   if (!strcmp(e, "256w8t")) return GEMM_256_W8T;
   if (!strcmp(e, "256pp")) return GEMM_256_PP;
   if (!strcmp(e, "256w4")) return GEMM_256_W4;
+  if (!strcmp(e, "256pp16")) return GEMM_256_PP16;
   if (!strcmp(e, "skinny")) return GEMM_SKINNY;
   if (!strcmp(e, "skinnydma")) return GEMM_SKINNY_DMA;
   if (!strcmp(e, "skinnydmaw")) return GEMM_SKINNY_DMAW;

@@ -17,6 +17,7 @@ enum GemmVariant {
   GEMM_SKINNY_DMA = 8,  // same shapes, B streamed through an LDS ring: 16 columns x 512 k per stage
   GEMM_SKINNY_DMAW = 9, // the same with 64 columns x 128 k per stage
   GEMM_256_W4 = 10,   // 256x256x64, 4 wavefronts (2x2) of 128x128, software-pipelined, direct-to-LDS loads
+  GEMM_256_PP16 = 11, // the two-group kernel on 16x16x32 MFMAs
   GEMM_NUM_VARIANTS
 };
 
@@ -44,7 +45,7 @@ struct GemmPlan {
 GemmPlan plan_gemm(const GemmArgs& g);
 int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s);
 bool gemm_pp_ok(const GemmArgs& g);            // gemm_pp.hip: can the two-group kernel take this problem?
-int run_gemm_pp(const GemmArgs& g, hipStream_t s);
+int run_gemm_pp(const GemmArgs& g, int mfma_size, hipStream_t s);   // mfma_size 32: 32x32x16, 16: 16x16x32
 int run_gemm_w4(const GemmArgs& g, hipStream_t s);   // gemm_w4.hip; same operand requirements (gemm_pp_ok)
 bool gemm_skinny_ok(const GemmArgs& g);        // gemm_skinny.hip
 int run_gemm_skinny(const GemmArgs& g, hipStream_t s);

@@ -105,7 +105,8 @@ def test_tiling_query_is_the_papers_partition_rule(binding):
     wg, waves, per_wave, mfma = t[0:2], t[2:4], t[4:6], t[6:9]
     assert wg == [256, 256] and waves[0] * waves[1] == 8
     assert per_wave == [wg[0] // waves[0], wg[1] // waves[1]]
-    assert mfma == [32, 32, 16] and per_wave[0] % 32 == 0 and per_wave[1] % 32 == 0
+    # the hardware dot of the big-tile kernel is the 16x16x32 MFMA (the lower-power shape)
+    assert mfma == [16, 16, 32] and per_wave[0] % 16 == 0 and per_wave[1] % 16 == 0
     small = binding.mlt_query_tiling(0, (512, 512, 512, 1), 1)
     assert small[0:2] == [128, 128]
     a = binding.mlt_query_tiling(1, (4096, 4096, 128, 0), 0)

@@ -54,11 +54,13 @@ def test_exact_tiles(variant, transB):
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("shape", [(520, 776, 320), (512, 768, 256), (100, 40, 64), (257, 264, 128)])
-def test_two_group_kernel(shape, transB, dtype):
-    # the direct-to-LDS two-group kernel: K a multiple of 64, ragged and exact M/N, one and many K steps
+@pytest.mark.parametrize("form", ["256pp", "256pp16"])
+def test_two_group_kernel(shape, transB, dtype, form):
+    # the direct-to-LDS two-group kernel in both MFMA shapes (32x32x16, 16x16x32): K a multiple of
+    # 64, ragged and exact M/N, one and many K steps
     M, N, K = shape
-    name, _ = _go(M, N, K, dtype, transB, variant="256pp", seed=6)
-    assert name.endswith("_pp")
+    name, _ = _go(M, N, K, dtype, transB, variant=form, seed=6)
+    assert name.endswith("_pp16" if form == "256pp16" else "_pp")
 
 
 @pytest.mark.parametrize("transB", [False, True])
