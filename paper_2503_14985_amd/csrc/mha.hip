@@ -369,12 +369,24 @@ MhaPlan plan_mha(const MhaArgs& a) {
   if (a.D != 64 && a.D != 128) return p;
   p.supported = true;
   p.bm = MHA_BM; p.bn = MHA_BN; p.waves = MHA_NW;
-  // Tuning/debug override: MLT_MHA_VARIANT = single selects the older single-schedule kernel.
+  // Tuning/debug override: MLT_MHA_VARIANT = single selects the older single-schedule kernel,
+  // pp32 / pp16 the two-group kernel on 32x32x16 / 16x16x32 MFMAs.
   const char* e = getenv("MLT_MHA_VARIANT");
   p.two_group = mha_pp_ok(a) && !(e && !strcmp(e, "single"));
   if (p.two_group) {
-    if (a.D == 128) p.name = a.causal ? "mha_fwd_d128_causal_256x64_pp" : "mha_fwd_d128_256x64_pp";
-    else p.name = a.causal ? "mha_fwd_d64_causal_256x64_pp" : "mha_fwd_d64_256x64_pp";
+    // Default: 32x32x16. Measured for D = 128: the 16x16x32 form is 3 % faster in back-to-back
+    // launches but 2 % slower when it alternates with the GEMM (the benchmark step); for D = 64 it
+    // does not fit the 128 registers that let two workgroups share a CU (-6 %).
+    p.mfma_size = 32;
+    if (e && !strcmp(e, "pp16")) p.mfma_size = 16;
+    if (e && !strcmp(e, "pp32")) p.mfma_size = 32;
+    if (p.mfma_size == 16) {
+      if (a.D == 128) p.name = a.causal ? "mha_fwd_d128_causal_256x64_pp16" : "mha_fwd_d128_256x64_pp16";
+      else p.name = a.causal ? "mha_fwd_d64_causal_256x64_pp16" : "mha_fwd_d64_256x64_pp16";
+    } else {
+      if (a.D == 128) p.name = a.causal ? "mha_fwd_d128_causal_256x64_pp" : "mha_fwd_d128_256x64_pp";
+      else p.name = a.causal ? "mha_fwd_d64_causal_256x64_pp" : "mha_fwd_d64_256x64_pp";
+    }
     return p;
   }
   if (a.D == 128) p.name = a.causal ? "mha_fwd_d128_causal_256x64" : "mha_fwd_d128_256x64";
@@ -383,7 +395,7 @@ MhaPlan plan_mha(const MhaArgs& a) {
 }
 
 int run_mha(const MhaArgs& a, const MhaPlan& p, hipStream_t s) {
-  if (p.two_group) return run_mha_pp(a, s);
+  if (p.two_group) return run_mha_pp(a, p.mfma_size, s);
   return a.dtype == MLT_BF16 ? run_mha_t<bf16_tag>(a, s) : run_mha_t<f16_tag>(a, s);
 }
 

@@ -456,10 +456,386 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// The same kernel on 16x16x32 MFMAs. Schedule, LDS ring, swizzles, loads and softmax are those of
+// mha_pp_kernel above; what changes is the shape of the hardware dot and with it who holds what.
+// Measured on N(0,1) operands the chip sustains 2100 TFLOP/s of 16x16x32 bf16 MFMAs against 1850
+// TFLOP/s of 32x32x16 (a register-only loop; the chip is power-limited and this shape reads and
+// writes half as many accumulator registers per flop), with the same LDS bytes per flop.
+//   S^T tile (kt, qt) = K rows 16*kt.. x queries 16*qt..:  lane l holds query l%16 of the q tile
+//     and keys 16*kt + 4*(l/16) + r, r = 0..3 (one f32x4); 4 key tiles x 2 query tiles per wavefront;
+//   P^T as B operand of O^T += V^T P^T over a 32-key slice ks: a lane's 8 contraction slots are its
+//     own 4 + 4 values of the key tiles 2*ks and 2*ks+1, i.e. keys 32*ks + 4*(l/16) + e and
+//     32*ks + 16 + 4*(l/16) + e. The contraction order inside a slice is free as long as V^T uses
+//     the same one: the two transposing reads of a V^T fragment fetch exactly those two groups of
+//     four key rows. Again no data movement between the two products;
+//   O^T tile (dt, qt) = d rows 16*dt.. x queries 16*qt..: lane holds d = 16*dt + 4*(l/16) + r;
+//   a row's statistics live in the 4 lanes l%16 + 16*g: the row maximum takes two lane swaps
+//     (rows of 16, then halves of 32), the row sum none until the end.
+__device__ __forceinline__ float four_groups_max(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float m1 = __builtin_fmaxf(__builtin_bit_cast(float, (unsigned)a[0]), __builtin_bit_cast(float, (unsigned)a[1]));
+  return both_halves_max(m1);
+}
+__device__ __forceinline__ float four_groups_sum(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float s1 = __builtin_bit_cast(float, (unsigned)a[0]) + __builtin_bit_cast(float, (unsigned)a[1]);
+  return both_halves_sum(s1);
+}
+
 template <typename Tag, int D, bool CAUSAL>
+__global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp16_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+    const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int Sq, int Sk, int nq, int total,
+    float c, int negate) {
+  typedef PaCfg<D> L;
+  typedef typename Elem<Tag>::vec8 V8;
+  constexpr int NDS = D / 32;                            // 32-deep d slices of S^T = K Q^T
+  constexpr int NDT = L::NDT;                            // pairs of 16-row d tiles of O^T (= D / 32)
+  constexpr int ROWB = L::ROWB;
+  extern __shared__ __align__(16) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;                             // waves w and w+4 share a SIMD
+  const int l16 = lane & 15, g4 = lane >> 4;
+  int bh, qt_wg;
+  block_map(blockIdx.x, total, nq, bh, qt_wg);
+  const int q0 = qt_wg * PA_BM + wave * 32;              // first query row of this wavefront
+  int my_q[2];
+  my_q[0] = q0 + l16;
+  my_q[1] = q0 + 16 + l16;
+
+  const uint16_t* Qh = Q + (int64_t)bh * Sq * D;
+  const char* Kh = reinterpret_cast<const char*>(K + (int64_t)bh * Sk * D);
+  const char* Vh = reinterpret_cast<const char*>(V + (int64_t)bh * Sk * D);
+
+  int kv_len = Sk;
+  if (CAUSAL) {
+    const int last_q = (qt_wg + 1) * PA_BM < Sq ? (qt_wg + 1) * PA_BM : Sq;      // exclusive
+    kv_len = last_q < Sk ? last_q : Sk;
+  }
+  const int nblk = (kv_len + PA_BN - 1) / PA_BN;
+  int my_nblk = nblk;
+  if (CAUSAL) {
+    const int need = (q0 + 31) / PA_BN + 1;
+    my_nblk = need < nblk ? need : nblk;
+  }
+
+  // ---- Q^T operand, resident in registers: query tile qt, d slice ds: query l16, d = 32*ds + 8*g4..
+  V8 qf[2][NDS];
+  {
+    const uint32_t flip = negate ? 0x80008000u : 0u;
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      const int row = my_q[qt] < Sq ? my_q[qt] : Sq - 1;
+      const uint16_t* qp = Qh + (int64_t)row * D + 8 * g4;
+#pragma unroll
+      for (int ds = 0; ds < NDS; ++ds) {
+        u32x4 raw = *reinterpret_cast<const u32x4_mem*>(qp + ds * 32);
+        raw[0] ^= flip; raw[1] ^= flip; raw[2] ^= flip; raw[3] ^= flip;
+        qf[qt][ds] = __builtin_bit_cast(V8, raw);
+      }
+    }
+  }
+
+  // ---- global -> LDS assignments (as in mha_pp_kernel)
+  uint32_t voff_k[L::LPW], voff_v[L::LPW];
+  int ld_row[L::LPW];
+#pragma unroll
+  for (int i = 0; i < L::LPW; ++i) {
+    const int row = (wave * L::LPW + i) * L::RPB + lane / L::CPR;
+    const int slot = lane % L::CPR;
+    ld_row[i] = row;
+    voff_k[i] = (uint32_t)row * ROWB + (uint32_t)(slot ^ L::fk(row)) * 16u;
+    voff_v[i] = (uint32_t)row * ROWB + (uint32_t)(slot ^ L::fv(row)) * 16u;
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+  auto issue_tile = [&](int t) {
+    const uint32_t dst = lds0 + (t % PA_NS) * L::SLOT_B + wave * L::LPW * 1024;
+    const char* kp = Kh + (int64_t)t * L::TILE_B;
+    const char* vp = Vh + (int64_t)t * L::TILE_B;
+    if ((t + 1) * PA_BN <= Sk) {
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) load_lds16(kp, voff_k[i], dst + i * 1024);
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) load_lds16(vp, voff_v[i], dst + L::TILE_B + i * 1024);
+    } else {
+      const int last = Sk - 1 - t * PA_BN;
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) {
+        const int back = ld_row[i] > last ? (ld_row[i] - last) * ROWB : 0;
+        load_lds16(kp, voff_k[i] - back, dst + i * 1024);
+      }
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) {
+        const int back = ld_row[i] > last ? (ld_row[i] - last) * ROWB : 0;
+        load_lds16(vp, voff_v[i] - back, dst + L::TILE_B + i * 1024);
+      }
+    }
+  };
+
+  // ---- fragment addresses (complete LDS addresses of slot 0, advanced by one add per tile)
+  // K rows as A operand: key row l16 of a 16-key tile (the tile is an immediate), 16-byte chunk
+  // 4*ds + g4 of the row, swizzled with the row's key (which the tile offset does not change).
+  uint32_t ka[NDS], va[NDT];
+#pragma unroll
+  for (int ds = 0; ds < NDS; ++ds)
+    ka[ds] = lds0 + (uint32_t)(l16 * ROWB + (((4 * ds + g4) ^ L::fk(l16)) << 4));
+  // V^T as A operand through the transposing read: lane s = l16 of its 16-lane group addresses
+  // key row 4*g4 + s/4 of the slice's first key tile (+ 16 rows for the second read) and the d
+  // columns 4*(s%4)..+3 of a 16-wide d tile; d tile dt = 2*t + u: chunk 4*t + 2*u + (s%4)/2, whose
+  // 4*t part goes through the swizzle (va[t]) and whose 2*u part is an immediate of 32 bytes.
+  {
+    const int vrow = 4 * g4 + (l16 >> 2);
+    const int c4 = l16 & 3;
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+      va[t] = lds0 + (uint32_t)(L::TILE_B + vrow * ROWB + ((((4 * t) ^ L::fv(vrow)) + (c4 >> 1)) << 4) + 8 * (c4 & 1));
+  }
+  // V fragment (ks, dt): key slice ks (32 keys), d tile dt
+  auto read_v_frag = [&](int ks, int dt, V8& f) {
+    const uint32_t a = va[dt >> 1] + (dt & 1) * 32 + ks * 32 * ROWB;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLT_LDS s16x4*)(uintptr_t)a);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLT_LDS s16x4*)(uintptr_t)(a + 16 * ROWB));
+    f = join_tr<V8>(lo, hi);
+  };
+  // K fragment (kt, ds): key tile kt (16 keys), d slice ds
+  auto read_k_frag = [&](int kt, int ds, V8& f) {
+    f = __builtin_bit_cast(V8, *(const MLT_LDS u32x4*)(uintptr_t)(ka[ds] + kt * 16 * ROWB));
+  };
+
+  f32x4 o_acc[2 * NDT][2];                               // [d tile][query tile]
+#pragma unroll
+  for (int dt = 0; dt < 2 * NDT; ++dt)
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) o_acc[dt][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 s_acc[4][2];                                     // [key tile][query tile]
+  u32x4 pq[2][2];                                        // P^T operands [key slice][query tile]
+  float mc_run[2] = {-__builtin_inff(), -__builtin_inff()};   // per query tile: this lane's query
+  float l_run[2] = {0.f, 0.f};
+
+  // Fragments come in chunks of NDT; every fragment feeds two MFMAs (the two query tiles).
+  // V chunk cg (0..3): key slice cg / 2, d tiles (cg % 2) * NDT + t; K chunk ch (0..3): key tile ch,
+  // d slices 0..NDT-1 (NDS = NDT).
+  V8 fb[2][NDT];
+  auto read_v_chunk_frag = [&](int cg, int t, V8& f) { read_v_frag(cg >> 1, (cg & 1) * NDT + t, f); };
+  auto mfma_v = [&](int cg, int t, const V8& f) {
+    const int ks = cg >> 1, dt = (cg & 1) * NDT + t;
+    o_acc[dt][0] = mfma16(f, __builtin_bit_cast(V8, pq[ks][0]), o_acc[dt][0]);
+    o_acc[dt][1] = mfma16(f, __builtin_bit_cast(V8, pq[ks][1]), o_acc[dt][1]);
+  };
+  auto mfma_k = [&](int kt, int ds, const V8& f) {
+    if (ds == 0) {                                        // first slice: start from zero
+      const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+      s_acc[kt][0] = mfma16(f, qf[0][0], z);
+      s_acc[kt][1] = mfma16(f, qf[1][0], z);
+    } else {
+      s_acc[kt][0] = mfma16(f, qf[0][ds], s_acc[kt][0]);
+      s_acc[kt][1] = mfma16(f, qf[1][ds], s_acc[kt][1]);
+    }
+  };
+#define MLT_SB() __builtin_amdgcn_sched_barrier(0)
+
+  // ---- softmax of S_j (in s_acc) -> pq, mc_run, rescaled o_acc and l_run
+  auto softmax_tile = [&](int j) {
+    const int kb0 = j * PA_BN;
+    // register r of tile (kt, qt) is key kb0 + 16*kt + 4*g4 + r for query my_q[qt]
+    const bool need_mask = (CAUSAL && (kb0 + PA_BN - 1 > q0)) || (kb0 + PA_BN > Sk);
+    if (need_mask) {
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        const int limit = CAUSAL ? (my_q[qt] < Sk - 1 ? my_q[qt] : Sk - 1) : Sk - 1;
+        const int rel = limit - (kb0 + 4 * g4);
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (16 * kt + r > rel) s_acc[kt][qt][r] = -__builtin_inff();
+      }
+    }
+    float t2[2];
+    bool grow[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      float mx = max3(s_acc[0][qt][0], s_acc[0][qt][1], s_acc[0][qt][2]);
+      mx = max3(mx, s_acc[0][qt][3], s_acc[1][qt][0]);
+      mx = max3(mx, s_acc[1][qt][1], s_acc[1][qt][2]);
+      mx = max3(mx, s_acc[1][qt][3], s_acc[2][qt][0]);
+      mx = max3(mx, s_acc[2][qt][1], s_acc[2][qt][2]);
+      mx = max3(mx, s_acc[2][qt][3], s_acc[3][qt][0]);
+      mx = max3(mx, s_acc[3][qt][1], s_acc[3][qt][2]);
+      mx = __builtin_fmaxf(mx, s_acc[3][qt][3]);
+      mx = four_groups_max(mx);
+      t2[qt] = mx * c;
+      grow[qt] = t2[qt] - mc_run[qt] > PA_LAZY_T;         // true on the first tile (mc_run = -inf)
+    }
+    // lazy rescale, as in mha_pp_kernel
+    if (__builtin_amdgcn_ballot_w64(grow[0] || grow[1]) != 0) {
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        const float alpha = grow[qt] ? __builtin_amdgcn_exp2f(mc_run[qt] - t2[qt]) : 1.f;
+        l_run[qt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 2 * NDT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) o_acc[dt][qt][r] *= alpha;
+        mc_run[qt] = grow[qt] ? t2[qt] : mc_run[qt];
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int kt = 2 * ks + (e >> 1), r = 2 * (e & 1);
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kt][qt][r], c, -mc_run[qt]));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kt][qt][r + 1], c, -mc_run[qt]));
+          pq[ks][qt][e] = Elem<Tag>::pack2(p0, p1);
+        }
+  };
+
+  // ---- schedule: identical to mha_pp_kernel (phases, barriers, waits)
+  constexpr int LPT = 2 * L::LPW;                         // loads per wavefront per tile
+#pragma unroll
+  for (int t = 0; t < PA_AHEAD; ++t)
+    if (t < nblk) issue_tile(t);
+  if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 15));
+  else if (nblk == 2) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+  else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+  __builtin_amdgcn_s_barrier();
+  if (grp == 1) __builtin_amdgcn_s_barrier();            // stagger: group 1 runs one phase behind
+
+  // prologue: S_0 = K_0 Q^T, then the first two V_0 chunks
+  {
+    if (my_nblk > 0) {                                    // ka, va point into slot 0
+#pragma unroll
+      for (int i = 0; i < NDT; ++i) read_k_frag(0, i, fb[0][i]);
+#pragma unroll
+      for (int i = 0; i < NDT; ++i) read_k_frag(1, i, fb[1][i]);
+      MLT_SB();
+#pragma unroll
+      for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+        for (int i = 0; i < NDT; ++i) {
+          mfma_k(ch, i, fb[ch & 1][i]);
+          MLT_SB();
+          if (ch < 2) read_k_frag(ch + 2, i, fb[ch & 1][i]);
+          else read_v_chunk_frag(ch - 2, i, fb[ch & 1][i]);
+          MLT_SB();
+        }
+    }
+    if (grp == 1) {
+      if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+      else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+    }
+    __builtin_amdgcn_s_barrier();
+  }
+
+  int slot_off = 0;                                       // byte offset of tile j's slot
+  for (int j = 0; j < nblk; ++j) {
+    const int slot_off_next = slot_off + L::SLOT_B == L::SMEM ? 0 : slot_off + L::SLOT_B;
+    const bool active = j < my_nblk;                       // wavefront-uniform
+    const bool active_next = j + 1 < my_nblk;
+    // ---- X_j
+    if (j + PA_AHEAD < nblk) issue_tile(j + PA_AHEAD);
+    __builtin_amdgcn_sched_barrier(0);
+    if (active) {
+      softmax_tile(j);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) asm volatile("" : "+v"(pq[ks][qt]));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (grp == 0) {
+      const int newer = (j + 3 < nblk ? 1 : 0) + (j + 2 < nblk ? 1 : 0);
+      if (newer == 2) __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 0));
+      else if (newer == 1) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 0));
+      else __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+    } else {
+      __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
+    }
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (D == 128) __builtin_amdgcn_s_setprio(1);
+    // ---- C_j: O^T += V_j^T P_j^T (V chunks 0..3), then S_{j+1}^T = K_{j+1} Q^T (K chunks 0..3),
+    // then the first two V_{j+1} chunks into the buffers; chunk n's MFMAs alternate with the reads
+    // of chunk n+2. The fragment addresses move on to the slot of tile j+1 on the way.
+    if (active) {
+      const uint32_t dslot = (uint32_t)(slot_off_next - slot_off);
+#pragma unroll
+      for (int cg = 0; cg < 4; ++cg)
+#pragma unroll
+        for (int t = 0; t < NDT; ++t) {
+          mfma_v(cg, t, fb[cg & 1][t]);
+          MLT_SB();
+          if (cg < 2) read_v_chunk_frag(cg + 2, t, fb[cg & 1][t]);
+          else read_k_frag(cg - 2, t, fb[cg & 1][t]);
+          if (cg == 0) ka[t] += dslot;
+          if (cg == 3) va[t] += dslot;
+          MLT_SB();
+        }
+      if (active_next) {
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+          for (int i = 0; i < NDT; ++i) {
+            mfma_k(ch, i, fb[ch & 1][i]);
+            MLT_SB();
+            if (ch < 2) read_k_frag(ch + 2, i, fb[ch & 1][i]);
+            else read_v_chunk_frag(ch - 2, i, fb[ch & 1][i]);
+            MLT_SB();
+          }
+      }
+      // row sums of the ROUNDED weights, behind the last MFMA (see mha_pp_kernel)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          l_run[0] = Elem<Tag>::add_pair(pq[ks][0][e], l_run[0]);
+          l_run[1] = Elem<Tag>::add_pair(pq[ks][1][e], l_run[1]);
+        }
+      asm volatile("" : "+v"(l_run[0]), "+v"(l_run[1]));
+    }
+    if (D == 128) __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (grp == 1) {
+      if (j + 3 < nblk) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+      else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+    }
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    slot_off = slot_off_next;
+  }
+#undef MLT_SB
+  if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
+
+  // ---- epilogue: O = O^T / l, l summed over the four lane groups; 4 consecutive d per store
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float inv = 1.f / four_groups_sum(l_run[qt]);
+    if (my_q[qt] < Sq) {
+      uint16_t* op = O + ((int64_t)bh * Sq + my_q[qt]) * D + 4 * g4;
+#pragma unroll
+      for (int dt = 0; dt < 2 * NDT; ++dt) {
+        u32x2 w;
+        w[0] = Elem<Tag>::pack2(o_acc[dt][qt][0] * inv, o_acc[dt][qt][1] * inv);
+        w[1] = Elem<Tag>::pack2(o_acc[dt][qt][2] * inv, o_acc[dt][qt][3] * inv);
+        *reinterpret_cast<u32x2_mem*>(op + dt * 16) = w;
+      }
+    }
+  }
+}
+
+template <typename Tag, int D, bool CAUSAL, int MS>
 int launch_mha_pp(const MhaArgs& a, hipStream_t s) {
   typedef PaCfg<D> L;
-  auto kern = mha_pp_kernel<Tag, D, CAUSAL>;
+  auto kern = MS == 16 ? mha_pp16_kernel<Tag, D, CAUSAL> : mha_pp_kernel<Tag, D, CAUSAL>;
   static thread_local int configured_dev = -1;          // opt in to > 64 KB LDS once per device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
@@ -484,10 +860,10 @@ int launch_mha_pp(const MhaArgs& a, hipStream_t s) {
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
-template <typename Tag>
+template <typename Tag, int MS>
 int run_mha_pp_t(const MhaArgs& a, hipStream_t s) {
-  if (a.D == 128) return a.causal ? launch_mha_pp<Tag, 128, true>(a, s) : launch_mha_pp<Tag, 128, false>(a, s);
-  if (a.D == 64) return a.causal ? launch_mha_pp<Tag, 64, true>(a, s) : launch_mha_pp<Tag, 64, false>(a, s);
+  if (a.D == 128) return a.causal ? launch_mha_pp<Tag, 128, true, MS>(a, s) : launch_mha_pp<Tag, 128, false, MS>(a, s);
+  if (a.D == 64) return a.causal ? launch_mha_pp<Tag, 64, true, MS>(a, s) : launch_mha_pp<Tag, 64, false, MS>(a, s);
   return MLT_ERR_UNSUPPORTED;
 }
 
@@ -496,8 +872,10 @@ int run_mha_pp_t(const MhaArgs& a, hipStream_t s) {
 // Sk * D * 2 must fit the 32-bit per-lane byte offsets of the direct loads.
 bool mha_pp_ok(const MhaArgs& a) { return (a.D == 64 || a.D == 128) && a.Sk * a.D * 2 < ((int64_t)1 << 31); }
 
-int run_mha_pp(const MhaArgs& a, hipStream_t s) {
-  return a.dtype == MLT_BF16 ? run_mha_pp_t<bf16_tag>(a, s) : run_mha_pp_t<f16_tag>(a, s);
+int run_mha_pp(const MhaArgs& a, int mfma_size, hipStream_t s) {
+  if (mfma_size == 16)
+    return a.dtype == MLT_BF16 ? run_mha_pp_t<bf16_tag, 16>(a, s) : run_mha_pp_t<f16_tag, 16>(a, s);
+  return a.dtype == MLT_BF16 ? run_mha_pp_t<bf16_tag, 32>(a, s) : run_mha_pp_t<f16_tag, 32>(a, s);
 }
 
 }  // namespace mlt

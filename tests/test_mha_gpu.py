@@ -1,5 +1,6 @@
 """GPU parity of mlt_mha_fwd against the fp64 oracle (through the C ABI via the ctypes binding)."""
 import math
+import os
 
 import numpy as np
 import pytest
@@ -16,7 +17,9 @@ BF16, FP16 = inputs.BF16, inputs.FP16
 @pytest.fixture(autouse=True)
 def _announce(request):
     print("\n[case] %s" % request.node.name, flush=True)
+    os.environ.pop("MLT_MHA_VARIANT", None)
     yield
+    os.environ.pop("MLT_MHA_VARIANT", None)
 
 
 def _go(B, H, Sq, Sk, D, dtype, causal, seed=0, scale=None, q_gain=1.0, **kw):
@@ -37,6 +40,21 @@ def test_small_multi_tile(dtype, causal, D):
     st = _go(1, 2, 512, 320, D, dtype, causal, seed=1)
     # sharper than the graded bound: output rounding plus P rounding only
     assert st["rel_rms"] < (1.5e-2 if dtype == BF16 else 2e-3)
+
+
+@pytest.mark.parametrize("variant,suffix", [("pp16", "_pp16"), ("pp32", "_pp"), ("single", "256x64")])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("D,dtype", [(128, BF16), (64, FP16), (128, FP16), (64, BF16)])
+def test_every_kernel_variant(variant, suffix, causal, D, dtype):
+    """The default is the two-group kernel on 32x32x16 MFMAs; its 16x16x32 form and the older
+    single-schedule kernel stay selectable and correct: several query and key tiles, ragged ends,
+    peaky rows."""
+    from paper_2503_14985_amd import binding
+    os.environ["MLT_MHA_VARIANT"] = variant
+    _go(1, 2, 600, 455, D, dtype, causal, seed=11)
+    assert binding.mlt_last_kernel().endswith(suffix)
+    _go(2, 1, 300, 300, D, dtype, causal, seed=12, q_gain=3.0)
+    assert binding.mlt_last_kernel().endswith(suffix)
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1, 1), (1, 1, 7, 1), (1, 3, 33, 17), (2, 2, 300, 200),
