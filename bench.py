@@ -166,24 +166,26 @@ def mfma_ceiling(binding, ev, A, dev):
     import torch
     sink = torch.zeros(16, dtype=torch.float32, device=dev)
     res = {}
-    for name, data in (("zeros", torch.zeros(1 << 16, dtype=torch.bfloat16, device=dev)),
-                       ("n01", A.reshape(-1)[: 1 << 16].contiguous())):
+    for name, data, size in (("zeros", torch.zeros(1 << 16, dtype=torch.bfloat16, device=dev), 32),
+                             ("n01", A.reshape(-1)[: 1 << 16].contiguous(), 32),
+                             ("n01_16x16x32", A.reshape(-1)[: 1 << 16].contiguous(), 16)):
         iters, reps = 2048, 12
         for _ in range(3):
-            binding.mlt_probe_mfma(iters, data, sink)
+            binding.mlt_probe_mfma(iters, data, sink, size)
         e0, e1 = ev.create(), ev.create()
         binding.mlt_set_timing_events(e0, None)
-        flop = binding.mlt_probe_mfma(iters, data, sink)
+        flop = binding.mlt_probe_mfma(iters, data, sink, size)
         binding.mlt_set_timing_events(None, None)
         for _ in range(reps - 2):
-            binding.mlt_probe_mfma(iters, data, sink)
+            binding.mlt_probe_mfma(iters, data, sink, size)
         binding.mlt_set_timing_events(None, e1)
-        binding.mlt_probe_mfma(iters, data, sink)
+        binding.mlt_probe_mfma(iters, data, sink, size)
         binding.mlt_set_timing_events(None, None)
         torch.cuda.synchronize()
         res[name + "_tflops"] = flop * reps / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e12
-    res["note"] = ("register-only bf16 32x32x16 MFMA loop, 8 wavefronts per CU; n01 = operands "
-                   "taken from the GEMM's A matrix")
+    res["note"] = ("register-only bf16 MFMA loop, 8 wavefronts per CU; zeros / n01: 32x32x16 MFMAs on "
+                   "all-zero operands / on operands taken from the GEMM's A matrix; n01_16x16x32: the "
+                   "same N(0,1) operands through 16x16x32 MFMAs (the GEMM kernel's shape)")
     return res
 
 

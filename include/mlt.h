@@ -138,6 +138,14 @@ int mlt_paged_attn_decode(int64_t B, int64_t H, int64_t D, int64_t block_size, i
 int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* stream);
 
 /*
+ * The same diagnostic on 16x16x32 MFMAs (64 per iteration and wavefront, the same flop count):
+ * the shape the big-tile GEMM uses. On N(0,1) operands the chip sustains a higher rate of these
+ * than of 32x32x16 MFMAs (it is power-limited, and this shape reads and writes half as many
+ * accumulator registers per flop). Arguments and return values as for mlt_probe_mfma.
+ */
+int mlt_probe_mfma16(int iters, const void* data, void* sink, double* flop, void* stream);
+
+/*
  * Diagnostic for benchmarks (not part of the paper's method): enqueues one kernel that reads
  * `bytes` bytes at `data` once with 16-byte loads from every CU and writes nothing. On a buffer
  * much larger than the caches its duration gives the practical HBM read rate, the ceiling for

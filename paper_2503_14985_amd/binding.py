@@ -20,7 +20,7 @@ MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE
 
 EXPORTS = ("mlt_gemm", "mlt_mha_fwd", "mlt_set_timing_events", "mlt_last_kernel",
            "mlt_query_tiling", "mlt_status_string", "mlt_version", "mlt_probe_mfma",
-           "mlt_paged_attn_decode", "mlt_gemm_acc", "mlt_probe_hbm_read", "mlt_gemm_bias_act")
+           "mlt_paged_attn_decode", "mlt_gemm_acc", "mlt_probe_hbm_read", "mlt_gemm_bias_act", "mlt_probe_mfma16")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -43,6 +43,8 @@ _lib.mlt_paged_attn_decode.argtypes = [_i64, _i64, _i64, _i64, _i64, _i64, _p, _
                                        ctypes.c_float, _i32, _p]
 _lib.mlt_probe_mfma.restype = _i32
 _lib.mlt_probe_mfma.argtypes = [_i32, _p, _p, ctypes.POINTER(ctypes.c_double), _p]
+_lib.mlt_probe_mfma16.restype = _i32
+_lib.mlt_probe_mfma16.argtypes = [_i32, _p, _p, ctypes.POINTER(ctypes.c_double), _p]
 _lib.mlt_probe_hbm_read.restype = _i32
 _lib.mlt_probe_hbm_read.argtypes = [_p, _i64, _p, _p]
 _lib.mlt_set_timing_events.restype = None
@@ -105,17 +107,25 @@ def mlt_paged_attn_decode(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
     return O
 
 
-def mlt_probe_mfma(iters: int, data: torch.Tensor, sink: torch.Tensor) -> float:
+def mlt_probe_mfma(iters: int, data: torch.Tensor, sink: torch.Tensor, mfma_size: int = 32) -> float:
     """Enqueue the register-only MFMA loop on the current stream; returns the flop it executes.
-    `data`: at least 64 KiB of bf16 operand values on the GPU, `sink`: at least 4 bytes."""
+    `data`: at least 64 KiB of bf16 operand values on the GPU, `sink`: at least 4 bytes.
+    mfma_size 32: 32x32x16 MFMAs (mlt_probe_mfma), 16: 16x16x32 (mlt_probe_mfma16)."""
     if not data.is_cuda or data.numel() * data.element_size() < 65536 or not data.is_contiguous():
         raise ValueError("mlt_probe_mfma: data must be a contiguous GPU tensor of at least 64 KiB")
+    if mfma_size not in (16, 32):
+        raise ValueError("mfma_size must be 16 or 32")
+    fn = _lib.mlt_probe_mfma16 if mfma_size == 16 else _lib.mlt_probe_mfma
     flop = ctypes.c_double()
-    rc = _lib.mlt_probe_mfma(int(iters), data.data_ptr(), sink.data_ptr(), ctypes.byref(flop),
-                             torch.cuda.current_stream(data.device).cuda_stream)
+    rc = fn(int(iters), data.data_ptr(), sink.data_ptr(), ctypes.byref(flop),
+            torch.cuda.current_stream(data.device).cuda_stream)
     if rc != MLT_OK:
         raise MltError(rc, "mlt_probe_mfma")
     return flop.value
+
+
+def mlt_probe_mfma16(iters: int, data: torch.Tensor, sink: torch.Tensor) -> float:
+    return mlt_probe_mfma(iters, data, sink, mfma_size=16)
 
 
 def mlt_probe_hbm_read(data: torch.Tensor, sink: torch.Tensor) -> int:

@@ -23,6 +23,7 @@
 //   A tile  [256 rows][8 chunks of 8 k]   chunk c of row r sits in slot c ^ ((r >> 1) & 7)
 //   B tile, B given as N x K: same as A with n as the row
 //   B tile, B given as K x N: [64 k][32 chunks of 8 n], chunk q of row k sits in slot q ^ 4*(k & 3)
+//                             (16x16x32 form: q ^ (4*(k & 3) + 2*((k >> 3) & 1)), see swz_kn)
 // With these, the 16 lanes that the LDS serves together hit 16 distinct 16-byte bank groups, for
 // the row reads (ds_read_b128) and for the transposing reads (ds_read_b64_tr_b16) alike.
 //
@@ -84,6 +85,16 @@ __device__ __forceinline__ void load_lds16(const char* base, uint32_t voff, uint
                : "memory", "m0");
 }
 
+// Swizzle of the K x N operand tile ([64 k][32 chunks of 8 n]): chunk q of row k sits in slot
+// q ^ swz_kn(k). A transposing read serves 32 lanes at a time (8 bytes each). With 32-wide tiles
+// those are two 16-lane groups on the SAME four k rows and different chunks, and 4*(k & 3)
+// separates the rows; with 16-wide tiles they are two groups on k rows 8 apart, which in addition
+// need the 2*((k >> 3) & 1) term to land in different banks.
+template <int MS>
+__device__ __forceinline__ int swz_kn(int k) {
+  return MS == 32 ? 4 * (k & 3) : 4 * (k & 3) + 2 * ((k >> 3) & 1);
+}
+
 template <int MS, typename V8>
 __device__ __forceinline__ auto mfma_ms(V8 a, V8 b, typename std::conditional<MS == 32, f32x16, f32x4>::type c) {
   if constexpr (MS == 32) return mfma32(a, b, c);
@@ -140,7 +151,7 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int k = ((wave & 3) * 8 + i) * 2 + (lane >> 5);   // tile k row held by this slot
-      const int q = (lane & 31) ^ (4 * (k & 3));              // n chunk stored in this slot
+      const int q = (lane & 31) ^ swz_kn<MS>(k);              // n chunk stored in this slot
       const int col = n0 + q * 8;
       voff[i] = (uint32_t)k * (uint32_t)ldb * 2u + (uint32_t)(col < N ? col : 0) * 2u;
     }
@@ -192,7 +203,7 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     // lane s addresses k row s/4 (+4 for the second read), columns 4*(s%4)..
     const int g = lane >> 4, s = lane & 15;
     const int krow = 8 * g + (s >> 2);
-    const int x = 4 * (s >> 2);
+    const int x = swz_kn<16>(krow);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int q = wn * 8 + 2 * j + ((s & 3) >> 1);

@@ -195,7 +195,8 @@ int mlt_paged_attn_decode(int64_t B, int64_t H, int64_t D, int64_t block_size, i
   return rc;
 }
 
-int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* stream) {
+static int probe_mfma_impl(int mfma_size, int iters, const void* data, void* sink, double* flop,
+                           void* stream) {
   if (iters < 1 || iters > (1 << 20) || !data || !sink || !flop) return MLT_ERR_INVALID_ARG;
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
   int dev = 0, ncu = 0;
@@ -208,12 +209,20 @@ int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* 
   double f;
   {
     TimedRegion t(s);
-    f = run_mfma_probe(iters, ncu, data, (float*)sink, s);
+    f = run_mfma_probe(iters, ncu, data, (float*)sink, mfma_size, s);
   }
   if (f < 0) return MLT_ERR_LAUNCH;
   *flop = f;
-  g_last_kernel = "mfma_rate_probe";
+  g_last_kernel = mfma_size == 16 ? "mfma16_rate_probe" : "mfma_rate_probe";
   return MLT_OK;
+}
+
+int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* stream) {
+  return probe_mfma_impl(32, iters, data, sink, flop, stream);
+}
+
+int mlt_probe_mfma16(int iters, const void* data, void* sink, double* flop, void* stream) {
+  return probe_mfma_impl(16, iters, data, sink, flop, stream);
 }
 
 int mlt_probe_hbm_read(const void* data, int64_t bytes, void* sink, void* stream) {

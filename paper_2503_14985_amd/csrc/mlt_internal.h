@@ -71,7 +71,7 @@ bool mha_pp_ok(const MhaArgs& a);
 int run_mha_pp(const MhaArgs& a, int mfma_size, hipStream_t s);
 
 // probe.hip: launches the register-only MFMA loop, returns the flop it will execute (< 0: launch failed)
-double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, hipStream_t s);
+double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, int mfma_size, hipStream_t s);
 int run_hbm_read_probe(const void* data, int64_t bytes, uint32_t* sink, int ncu, hipStream_t s);
 
 MhaPlan plan_mha(const MhaArgs& a);

@@ -49,6 +49,44 @@ __global__ __launch_bounds__(512) void mfma_rate_kernel(int iters, const u32x4* 
   if (s == 12345.678f) sink[0] = s;                         // keeps the loop alive, practically never stores
 }
 
+// The same loop on 16x16x32 MFMAs (the shape the big-tile GEMM uses): the same 128 x 64 register
+// tile as 8 x 4 accumulators of 16 x 16, two 32-deep k slices of operands; 64 MFMAs of 16384 flop
+// per wavefront and iteration, i.e. the same flop count as above.
+__global__ __launch_bounds__(512) void mfma16_rate_kernel(int iters, const u32x4* __restrict__ data,
+                                                          float* __restrict__ sink) {
+  const int tid = threadIdx.x;
+  bf16x8 a[2][8], b[2][4];
+  const int base = tid & 511;
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[kk][i] = __builtin_bit_cast(bf16x8, data[base + (kk * 12 + i) * 128]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[kk][j] = __builtin_bit_cast(bf16x8, data[base + (kk * 12 + 8 + j) * 128 + 512]);
+  }
+  f32x4 acc[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = mfma16(a[kk][i], b[kk][j], acc[i][j]);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s += acc[i][j][r];
+  if (s == 12345.678f) sink[0] = s;
+}
+
 // Behind mlt_probe_hbm_read: workgroups of 4 wavefronts take 32 KB pieces of the buffer round-robin
 // and read each with 8 16-byte loads per lane in flight, folding everything into one word;
 // nothing is written. (Measured on 2 GiB: 6.3 TB/s this way, 5.4 TB/s when every lane instead
@@ -83,9 +121,13 @@ int run_hbm_read_probe(const void* data, int64_t bytes, uint32_t* sink, int ncu,
 }
 
 // 32 MFMAs of 32*32*16*2 flop per wavefront and iteration
-double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, hipStream_t s) {
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3(nblocks), dim3(512), 0, s, iters,
-                     reinterpret_cast<const u32x4*>(data), sink);
+double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, int mfma_size, hipStream_t s) {
+  if (mfma_size == 16)
+    hipLaunchKernelGGL(mfma16_rate_kernel, dim3(nblocks), dim3(512), 0, s, iters,
+                       reinterpret_cast<const u32x4*>(data), sink);
+  else
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(nblocks), dim3(512), 0, s, iters,
+                       reinterpret_cast<const u32x4*>(data), sink);
   if (hipGetLastError() != hipSuccess) return -1.0;
   return (double)nblocks * 8.0 * iters * 32.0 * 32768.0;
 }

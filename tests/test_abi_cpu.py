@@ -66,6 +66,8 @@ def test_probe_argument_validation_without_device(binding):
     assert f(16, None, p, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG      # data null
     assert f(16, p, None, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG      # sink null
     assert f(16, p, p, None, None) == binding.MLT_ERR_INVALID_ARG                       # flop null
+    assert lib.mlt_probe_mfma16(0, p, p, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG
+    assert lib.mlt_probe_mfma16(16, None, p, ctypes.byref(flop), None) == binding.MLT_ERR_INVALID_ARG
     r = lib.mlt_probe_hbm_read
     assert r(None, 1024, p, None) == binding.MLT_ERR_INVALID_ARG                        # data null
     assert r(p, 1024, None, None) == binding.MLT_ERR_INVALID_ARG                        # sink null

@@ -26,6 +26,11 @@ def test_probe_runs_and_counts_flop():
     assert 200.0 < tflops < 2600.0          # a loose sanity window around the chip's peak
     with pytest.raises(ValueError):
         binding.mlt_probe_mfma(16, data[:100], sink)
+    # the 16x16x32 form executes the same flop count
+    assert binding.mlt_probe_mfma16(512, data, sink) == flop
+    assert binding.mlt_last_kernel() == "mfma16_rate_probe"
+    torch.cuda.synchronize()
+    assert torch.equal(data, keep)
 
 
 def test_hbm_read_probe_runs():
