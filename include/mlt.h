@@ -67,6 +67,22 @@ int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
                  int64_t ldb, int transB, float* C, int64_t ldc, int dtype, void* stream);
 
 /*
+ * mlt_gemm with the paper's `tiling` hint (Section 3.1, "Compiler Hint"): how the wavefronts of a
+ * workgroup divide its 256 x 256 output tile. All settings compute the same C (up to summation
+ * order) and obey the same tolerances; what changes is the kernel.
+ *   tiling 0  the library's choice (the same as mlt_gemm)
+ *          1  horizontal: evenly along the rows only, 8 wavefronts x (32 x 256)
+ *          2  vertical: evenly along the columns only, 8 wavefronts x (256 x 32)
+ *          3  square: 2 x 2 wavefronts x (128 x 128)
+ * The hint applies to operands that allow 16-byte vector access (see mlt_gemm); others take the
+ * general kernel, K = 0 stores zeros, and M <= 64 with B stored N x K keeps the skinny kernels
+ * only for tiling 0. Returns as mlt_gemm; MLT_ERR_INVALID_ARG also for an unknown `tiling`.
+ */
+int mlt_gemm_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                   int64_t ldb, int transB, void* C, int64_t ldc, int dtype, int tiling,
+                   void* stream);
+
+/*
  * GEMM with a fused epilogue, C = act(A*B + bias): the post-operation fusion the paper expects to
  * fall out of its layout propagation from the root operation (Section 3.1, the remark on pre- and
  * post-operation fusion), here written into the kernels' epilogues. Arguments as for mlt_gemm,

@@ -20,7 +20,7 @@ MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE
 
 EXPORTS = ("mlt_gemm", "mlt_mha_fwd", "mlt_set_timing_events", "mlt_last_kernel",
            "mlt_query_tiling", "mlt_status_string", "mlt_version", "mlt_probe_mfma",
-           "mlt_paged_attn_decode", "mlt_gemm_acc", "mlt_probe_hbm_read", "mlt_gemm_bias_act", "mlt_probe_mfma16")
+           "mlt_paged_attn_decode", "mlt_gemm_acc", "mlt_probe_hbm_read", "mlt_gemm_bias_act", "mlt_probe_mfma16", "mlt_gemm_tiled")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -33,6 +33,8 @@ _lib.mlt_gemm.restype = _i32
 _lib.mlt_gemm.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _p]
 _lib.mlt_gemm_acc.restype = _i32
 _lib.mlt_gemm_acc.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _p]
+_lib.mlt_gemm_tiled.restype = _i32
+_lib.mlt_gemm_tiled.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _i32, _p]
 _lib.mlt_gemm_bias_act.restype = _i32
 _lib.mlt_gemm_bias_act.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i32, _p, _i64, _i32, _p]
 _lib.mlt_mha_fwd.restype = _i32
@@ -205,6 +207,32 @@ def mlt_gemm(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor | None = None, tr
 
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+TILING_AUTO, TILING_HORIZONTAL, TILING_VERTICAL, TILING_SQUARE = 0, 1, 2, 3
+
+
+def mlt_gemm_tiled(A: torch.Tensor, B: torch.Tensor, tiling: int, C: torch.Tensor | None = None,
+                   transB: bool = False, stream=None) -> torch.Tensor:
+    """mlt_gemm with the paper's tiling hint (TILING_AUTO / _HORIZONTAL / _VERTICAL / _SQUARE)."""
+    if not (A.is_cuda and B.is_cuda):
+        raise ValueError("mlt_gemm_tiled needs GPU tensors")
+    dt = _dtype_code(A)
+    if B.dtype != A.dtype:
+        raise TypeError("A and B must share a dtype")
+    M, K = A.shape
+    N, Kb = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
+    if K != Kb:
+        raise ValueError("inner dimensions differ: %d vs %d" % (K, Kb))
+    if C is None:
+        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    elif C.dtype != A.dtype or tuple(C.shape) != (M, N):
+        raise ValueError("C has the wrong dtype or shape")
+    lda, ldb, ldc = _rows_contiguous(A, "A"), _rows_contiguous(B, "B"), _rows_contiguous(C, "C")
+    with torch.cuda.device(A.device):
+        rc = _lib.mlt_gemm_tiled(M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, int(transB),
+                                 C.data_ptr(), ldc, dt, int(tiling), _stream(stream))
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_gemm_tiled")
+    return C
 
 
 def mlt_gemm_bias_act(A: torch.Tensor, B: torch.Tensor, bias: torch.Tensor | None = None,

@@ -452,6 +452,10 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       p.name = g.transB ? "gemm_nt_256x256x64_w4x2" : "gemm_nn_256x256x64_w4x2"; break;
     case GEMM_256_PP: p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x4_pp" : "gemm_nn_256x256x64_w2x4_pp"; break;
+    case GEMM_256_W8X1: p.bm = p.bn = 256; p.wm = 8; p.wn = 1;
+      p.name = g.transB ? "gemm_nt_256x256x64_w8x1" : "gemm_nn_256x256x64_w8x1"; break;
+    case GEMM_256_W1X8: p.bm = p.bn = 256; p.wm = 1; p.wn = 8;
+      p.name = g.transB ? "gemm_nt_256x256x64_w1x8" : "gemm_nn_256x256x64_w1x8"; break;
     case GEMM_256_PP16: p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
       p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x4_pp16" : "gemm_nn_256x256x64_w2x4_pp16"; break;
@@ -483,6 +487,8 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_256: return launch_tile_tb<Tag, 256, 256, 64, 2, 2>(g, s);
     case GEMM_256_W8: return launch_tile_tb<Tag, 256, 256, 64, 2, 4>(g, s);
     case GEMM_256_W8T: return launch_tile_tb<Tag, 256, 256, 64, 4, 2>(g, s);
+    case GEMM_256_W8X1: return launch_tile_tb<Tag, 256, 256, 64, 8, 1>(g, s);
+    case GEMM_256_W1X8: return launch_tile_tb<Tag, 256, 256, 64, 1, 8>(g, s);
     case GEMM_128: return launch_tile_tb<Tag, 128, 128, 64, 2, 2>(g, s);
     case GEMM_256_PP: return run_gemm_pp(g, 32, s);
     case GEMM_256_PP16: return run_gemm_pp(g, 16, s);

@@ -40,6 +40,8 @@ int forced_gemm_variant() {
   if (!strcmp(e, "256pp")) return GEMM_256_PP;
   if (!strcmp(e, "256w4")) return GEMM_256_W4;
   if (!strcmp(e, "256pp16")) return GEMM_256_PP16;
+  if (!strcmp(e, "256w8x1")) return GEMM_256_W8X1;
+  if (!strcmp(e, "256w1x8")) return GEMM_256_W1X8;
   if (!strcmp(e, "skinny")) return GEMM_SKINNY;
   if (!strcmp(e, "skinnydma")) return GEMM_SKINNY_DMA;
   if (!strcmp(e, "skinnydmaw")) return GEMM_SKINNY_DMAW;
@@ -113,6 +115,31 @@ int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
   GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
              (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 1};
+  GemmPlan p = plan_gemm(g);
+  hipStream_t s = (hipStream_t)stream;
+  {
+    TimedRegion t(s);
+    rc = run_gemm(g, p, s);
+  }
+  if (rc == MLT_OK) g_last_kernel = p.name;
+  return rc;
+}
+
+int mlt_gemm_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                   int64_t ldb, int transB, void* C, int64_t ldc, int dtype, int tiling,
+                   void* stream) {
+  int rc = check_gemm(M, N, K, A, lda, B, ldb, transB, C, ldc, dtype);
+  if (rc != MLT_OK) return rc;
+  if (tiling < 0 || tiling > 3) return MLT_ERR_INVALID_ARG;
+  if (M == 0 || N == 0) return MLT_OK;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
+             (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 0};
+  // horizontal: the wavefronts split the rows of the workgroup tile only; vertical: the columns
+  // only; square: 2 x 2 square sub-tiles (the pipelined kernel when the operands allow it)
+  if (tiling == 1) g.forced = GEMM_256_W8X1;
+  if (tiling == 2) g.forced = GEMM_256_W1X8;
+  if (tiling == 3) g.forced = gemm_pp_ok(g) ? GEMM_256_W4 : GEMM_256;
   GemmPlan p = plan_gemm(g);
   hipStream_t s = (hipStream_t)stream;
   {

@@ -18,6 +18,8 @@ enum GemmVariant {
   GEMM_SKINNY_DMAW = 9, // the same with 64 columns x 128 k per stage
   GEMM_256_W4 = 10,   // 256x256x64, 4 wavefronts (2x2) of 128x128, software-pipelined, direct-to-LDS loads
   GEMM_256_PP16 = 11, // the two-group kernel on 16x16x32 MFMAs
+  GEMM_256_W8X1 = 12, // 256x256x64, 8 wavefronts as 8x1: row strips of 32 x 256 ("horizontal")
+  GEMM_256_W1X8 = 13, // 256x256x64, 8 wavefronts as 1x8: column strips of 256 x 32 ("vertical")
   GEMM_NUM_VARIANTS
 };
 

@@ -56,6 +56,16 @@ def test_gemm_argument_validation_without_device(binding):
     assert g(8, 0, 8, null, 8, null, 16, 0, null, 16, 1, None) == binding.MLT_OK        # N = 0: no-op
 
 
+def test_tiling_hint_argument_validation_without_device(binding):
+    lib = binding.raw()
+    p = ctypes.c_void_p(0x1000)
+    t = lib.mlt_gemm_tiled
+    assert t(8, 8, 8, p, 8, p, 8, 0, p, 8, 0, 4, None) == binding.MLT_ERR_INVALID_ARG     # unknown tiling
+    assert t(8, 8, 8, p, 8, p, 8, 0, p, 8, 0, -1, None) == binding.MLT_ERR_INVALID_ARG
+    assert t(8, 8, 8, None, 8, p, 8, 0, p, 8, 0, 1, None) == binding.MLT_ERR_INVALID_ARG  # A null
+    assert t(0, 8, 8, None, 8, None, 8, 0, None, 8, 0, 2, None) == binding.MLT_OK         # M = 0: no-op
+
+
 def test_probe_argument_validation_without_device(binding):
     lib = binding.raw()
     p = ctypes.c_void_p(0x1000)

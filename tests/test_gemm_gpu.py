@@ -279,3 +279,26 @@ def test_fused_epilogue_edge_cases():
         binding.mlt_gemm_bias_act(A, B, torch.zeros(263, dtype=torch.float16, device=dev))
     with pytest.raises(ValueError):
         binding.mlt_gemm_bias_act(A, B, torch.zeros(264, dtype=torch.bfloat16, device=dev))
+
+
+@pytest.mark.parametrize("tiling,tag", [(0, None), (1, "_w8x1"), (2, "_w1x8"), (3, "_w2x2")])
+@pytest.mark.parametrize("transB", [False, True])
+def test_tiling_hint(tiling, tag, transB):
+    """The paper's tiling hint (Section 3.1): horizontal / vertical / square wave grids give the same
+    C within the tolerance, from different kernels; several tiles, ragged edges, ragged and exact K."""
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    for dtype, (M, N, K) in ((BF16, (520, 776, 320)), (FP16, (300, 264, 200)), (BF16, (16, 2048, 512))):
+        A, B = inputs.gemm_inputs(M, N, K, dtype, 13, transB=transB)
+        tA = inputs.bits_to_torch(A, dtype, dev)
+        tB = inputs.bits_to_torch(B, dtype, dev)
+        C = binding.mlt_gemm_tiled(tA, tB, tiling, transB=transB)
+        torch.cuda.synchronize()
+        name = binding.mlt_last_kernel()
+        st = pu.check_gemm(A, B, C, dtype, transB, seed=13)
+        print("   kernel=%s %s" % (name, st), flush=True)
+        if tag:
+            # K % 64 != 0 takes the register-staged 2 x 2 kernel, else the pipelined one
+            assert tag in name, name
+    with pytest.raises(binding.MltError):
+        binding.mlt_gemm_tiled(tA, tB, 4, transB=transB)
