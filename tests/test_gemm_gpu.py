@@ -183,6 +183,16 @@ def test_config3_llm_shapes_transB(shape):
     _go(M, N, K, BF16, True, std=0.02, seed=0)
 
 
+@pytest.mark.parametrize("shape,suffix", [((16, 28672, 8192), "16cols_stream"), ((1, 28672, 8192), "16cols_stream"),
+                                          ((64, 28672, 4096), "64cols_stream"), ((16, 131072, 4096), "16cols_stream")])
+def test_decode_shapes_streaming_kernels_full_size(shape, suffix):
+    # the memory-bound decode GEMMs at their real sizes, in the launch configuration the library
+    # picks (persistent workgroups, several column blocks each); sampled against the oracle
+    M, N, K = shape
+    name, _ = _go(M, N, K, BF16, True, std=0.02, seed=0)
+    assert name.endswith(suffix)
+
+
 @pytest.mark.parametrize("variant", [None, "256pp", "128", "general"])
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
