@@ -134,6 +134,22 @@ def test_padded_leading_dimensions(transB):
     assert "general" in name
 
 
+@pytest.mark.parametrize("variant,shape,transB", [("256pp16", (300, 264, 192), False), ("256pp16", (300, 264, 192), True),
+                                                  ("256pp", (300, 264, 192), False), ("256w4", (300, 264, 192), False),
+                                                  ("256w4", (300, 264, 192), True), ("skinnydma", (16, 1100, 1032), True),
+                                                  ("skinnydmaw", (40, 1100, 1032), True), ("skinny", (16, 1100, 1032), True)])
+def test_padded_leading_dimensions_direct_load_kernels(variant, shape, transB):
+    # row strides larger than the rows (NaN-filled padding that must never be read into a result
+    # or written) through the kernels that address global memory with per-lane byte offsets
+    M, N, K = shape
+    name, _ = _go(M, N, K, BF16, transB, seed=14, variant=variant, std=0.05,
+                  lda=K + 8, ldb=(K if transB else N) + 16, ldc_pad=5)
+    assert "general" not in name
+    name2, _ = _go(M, N, K, FP16, transB, seed=14, variant=variant, std=0.05,
+                   lda=K + 24, ldb=(K if transB else N) + 8, ldc_pad=3)
+    assert name2 == name
+
+
 def test_k_zero_and_empty():
     from paper_2503_14985_amd import binding
     dev = torch.device("cuda:0")
