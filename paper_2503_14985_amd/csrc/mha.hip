@@ -370,7 +370,8 @@ MhaPlan plan_mha(const MhaArgs& a) {
   p.supported = true;
   p.bm = MHA_BM; p.bn = MHA_BN; p.waves = MHA_NW;
   // Tuning/debug override: MLT_MHA_VARIANT = single selects the older single-schedule kernel,
-  // pp32 / pp16 the two-group kernel on 32x32x16 / 16x16x32 MFMAs.
+  // pp32 / pp16 the two-group kernel on 32x32x16 / 16x16x32 MFMAs, ps its persistent form (unmasked
+  // problems with at least two key tiles per item; other problems fall back to pp32).
   const char* e = getenv("MLT_MHA_VARIANT");
   p.two_group = mha_pp_ok(a) && !(e && !strcmp(e, "single"));
   if (p.two_group) {
@@ -380,6 +381,16 @@ MhaPlan plan_mha(const MhaArgs& a) {
     p.mfma_size = 32;
     if (e && !strcmp(e, "pp16")) p.mfma_size = 16;
     if (e && !strcmp(e, "pp32")) p.mfma_size = 32;
+    // The persistent form ("ps" forces it wherever it applies). Measured, unmasked, 2048 items:
+    // D = 128 gains 30 % at 2 key tiles per item, 18 % at 4, 8 % at 8, 4 % at 16, nothing from 32
+    // on (and loses 6 % at 64 tiles when the launches alternate with the GEMM); D = 64, where two
+    // workgroups per CU already cover each other's start and end, loses 10 % everywhere.
+    const bool ps_pays = a.D == 128 && a.Sk <= 16 * 64;
+    p.persistent = mha_ps_ok(a) && (e ? !strcmp(e, "ps") : ps_pays);
+    if (p.persistent) {
+      p.name = a.D == 128 ? "mha_fwd_d128_256x64_ps" : "mha_fwd_d64_256x64_ps";
+      return p;
+    }
     if (p.mfma_size == 16) {
       if (a.D == 128) p.name = a.causal ? "mha_fwd_d128_causal_256x64_pp16" : "mha_fwd_d128_256x64_pp16";
       else p.name = a.causal ? "mha_fwd_d64_causal_256x64_pp16" : "mha_fwd_d64_256x64_pp16";
@@ -395,6 +406,7 @@ MhaPlan plan_mha(const MhaArgs& a) {
 }
 
 int run_mha(const MhaArgs& a, const MhaPlan& p, hipStream_t s) {
+  if (p.persistent) return run_mha_ps(a, s);
   if (p.two_group) return run_mha_pp(a, p.mfma_size, s);
   return a.dtype == MLT_BF16 ? run_mha_t<bf16_tag>(a, s) : run_mha_t<f16_tag>(a, s);
 }

@@ -25,6 +25,10 @@
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4), into a ring of 5
 // slots (tile t in slot t % 5), fetched three tiles ahead. The tiles are stored unpadded; bank
 // conflicts are avoided by choosing which 16-byte chunk each lane fetches (XOR swizzles, below).
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "mlt_common.h"
 #include "mlt_internal.h"
 
@@ -458,6 +462,412 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
 
 
 // ---------------------------------------------------------------------------------------------
+// Persistent form of the kernel above for the unmasked case. A workgroup that handles one
+// (batch*head, query tile) item and exits pays, per item, for its launch, the latency of the Q
+// load, the latency of the first K/V tiles, the one-phase stagger of the two groups at both ends
+// and the draining of the O stores: about 10 us per item for D = 128, against 1.7 us per key tile.
+// Here the grid is one workgroup per CU (two for D = 64) and each workgroup walks through items
+// blockIdx.x, blockIdx.x + gridDim.x, ... as ONE stream of K/V tiles: the ring of LDS slots, the
+// prefetch distance and the phase structure run on across item boundaries, so the first tiles of
+// the next item are already in LDS when the current item ends. At a boundary
+//   - the softmax phase of an item's LAST tile also issues the loads of the next item's Q operand
+//     into the Q registers (they are dead from there on: S of the last tile has been computed),
+//   - the compute phase of that tile ends with S_0 of the NEXT item instead of S_{j+1},
+//   - the softmax phase of the next item's FIRST tile starts by normalising and storing the
+//     finished O tile and clearing the accumulators.
+// Only the first and the last item of a workgroup see a prologue, a stagger phase and a drain.
+//
+// Counting vector memory operations: besides the K/V loads the in-order queue that s_waitcnt
+// vmcnt looks at now also holds the Q loads and the O stores. An s_waitcnt vmcnt(N) is correct as
+// long as N does not exceed the number of operations issued after the one that is needed, so the
+// waits below add the Q loads / O stores to N only where they are certain to have been issued (a
+// wavefront whose query rows all lie beyond Sq issues no stores and adds nothing).
+template <typename Tag, int D>
+__global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_ps_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+    const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int Sq, int Sk, int nq, int total,
+    float c, int negate) {
+  typedef PaCfg<D> L;
+  typedef typename Elem<Tag>::vec8 V8;
+  constexpr int NKK = L::NKK, NDT = L::NDT, ROWB = L::ROWB;
+  constexpr int LPT = 2 * L::LPW;    // K/V loads per wavefront per tile
+  constexpr int NQL = NKK;           // loads per wavefront that fetch a Q operand
+  constexpr int NST = 4 * NDT;       // stores per wavefront that write an O tile
+  extern __shared__ __align__(16) char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;                             // waves w and w+4 share a SIMD
+  const int lq = lane & 31, h = lane >> 5;
+  const int G = (int)gridDim.x;
+  const int nblk = (Sk + PA_BN - 1) / PA_BN;             // key tiles per item, >= 2 (launcher)
+  const int n_items = (total - (int)blockIdx.x + G - 1) / G;   // >= 1 (launcher: G <= total)
+  const int NT = n_items * nblk;                         // tiles in this workgroup's stream
+
+  const char* Kb = reinterpret_cast<const char*>(K);
+  const char* Vb = reinterpret_cast<const char*>(V);
+  const int64_t head_b = (int64_t)Sk * ROWB;             // bytes of one head's K (or V)
+
+  // ---- Q^T operand of an item: query lq of the wavefront's 32 rows, d = 16*kk + 8*h .. +7.
+  // Loaded by inline assembly, so that the compiler does not track the loads: inside the loop it
+  // could only wait for them in every iteration, K/V loads included. q_issue starts the loads;
+  // the registers hold the operand only after the schedule's own wait and q_finish (which also
+  // applies a negative scale as a sign flip, so the softmax always sees c >= 0).
+  u32x4 qf[NKK];
+  const uint32_t flip = negate ? 0x80008000u : 0u;
+  auto q_issue = [&](int bh_, int q0_) __attribute__((always_inline)) {
+    const int my_q_ = q0_ + lq;
+    const int row = my_q_ < Sq ? my_q_ : Sq - 1;
+    const uint16_t* qp = Q + ((int64_t)bh_ * Sq + row) * D + 8 * h;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(qf[kk]) : "v"(qp + kk * 16) : "memory");
+  };
+  auto q_finish = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+      asm volatile("" : "+v"(qf[kk]));
+      qf[kk][0] ^= flip; qf[kk][1] ^= flip; qf[kk][2] ^= flip; qf[kk][3] ^= flip;
+    }
+  };
+
+  // ---- global -> LDS: wavefront w fills blocks w*LPW .. of the K tile and of the V tile; lane l
+  // owns the 16-byte slot l of a block.
+  uint32_t voff_k[L::LPW], voff_v[L::LPW];
+  int ld_row[L::LPW];
+#pragma unroll
+  for (int i = 0; i < L::LPW; ++i) {
+    const int row = (wave * L::LPW + i) * L::RPB + lane / L::CPR;
+    const int slot = lane % L::CPR;
+    ld_row[i] = row;
+    voff_k[i] = (uint32_t)row * ROWB + (uint32_t)(slot ^ L::fk(row)) * 16u;
+    voff_v[i] = (uint32_t)row * ROWB + (uint32_t)(slot ^ L::fv(row)) * 16u;
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+  // The prefetch cursor: stream tile pf_g = tile pf_j of item pf_item, goes to ring offset pf_slot.
+  int pf_g = 0, pf_j = 0, pf_item = (int)blockIdx.x, pf_slot = 0;
+  const char *pf_k, *pf_v;
+  {
+    int b0, t0;
+    block_map(pf_item, total, nq, b0, t0);
+    pf_k = Kb + (int64_t)b0 * head_b;
+    pf_v = Vb + (int64_t)b0 * head_b;
+  }
+  auto issue_next = [&]() __attribute__((always_inline)) {
+    if (pf_g >= NT) return;
+    const uint32_t dst = lds0 + pf_slot + wave * L::LPW * 1024;
+    const char* kp = pf_k + (int64_t)pf_j * L::TILE_B;
+    const char* vp = pf_v + (int64_t)pf_j * L::TILE_B;
+    if ((pf_j + 1) * PA_BN <= Sk) {
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) load_lds16(kp, voff_k[i], dst + i * 1024);
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) load_lds16(vp, voff_v[i], dst + L::TILE_B + i * 1024);
+    } else {
+      // ragged last tile: rows past Sk re-read row Sk-1 (their weights are forced to 0)
+      const int last = Sk - 1 - pf_j * PA_BN;
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) {
+        const int back = ld_row[i] > last ? (ld_row[i] - last) * ROWB : 0;
+        load_lds16(kp, voff_k[i] - back, dst + i * 1024);
+      }
+#pragma unroll
+      for (int i = 0; i < L::LPW; ++i) {
+        const int back = ld_row[i] > last ? (ld_row[i] - last) * ROWB : 0;
+        load_lds16(vp, voff_v[i] - back, dst + L::TILE_B + i * 1024);
+      }
+    }
+    ++pf_g;
+    pf_slot = pf_slot + L::SLOT_B == L::SMEM ? 0 : pf_slot + L::SLOT_B;
+    if (++pf_j == nblk) {
+      pf_j = 0;
+      pf_item += G;
+      if (pf_item < total) {
+        int b2, t2;
+        block_map(pf_item, total, nq, b2, t2);
+        pf_k = Kb + (int64_t)b2 * head_b;
+        pf_v = Vb + (int64_t)b2 * head_b;
+      }
+    }
+  };
+
+  // ---- fragment addresses (as in mha_pp_kernel)
+  const int k_frag = lq * ROWB + ((h ^ L::fk(lq)) << 4);
+  const int vg = lane >> 4, vs = lane & 15;
+  const int v_row = 4 * (vg >> 1) + (vs >> 2);
+  const int v_frag = L::TILE_B + v_row * ROWB + (((2 * (vg & 1) + ((vs & 3) >> 1)) ^ L::fv(v_row)) << 4) + 8 * (vs & 1);
+
+  f32x16 o_acc[NDT];
+#pragma unroll
+  for (int t = 0; t < NDT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o_acc[t][r] = 0.f;
+  f32x16 s_acc[2];
+  u32x4 pq[4];
+  float mc_run = -__builtin_inff();
+  float l_run = 0.f;
+
+  V8 fb[2][NDT];
+  uint32_t ka[NKK], va[NDT];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) ka[kk] = lds0 + (uint32_t)(k_frag ^ (kk << 5));
+#pragma unroll
+  for (int t = 0; t < NDT; ++t) va[t] = lds0 + (uint32_t)(v_frag ^ (t << 6));
+  auto read_v_frag = [&](int g, int t, V8& f) __attribute__((always_inline)) {
+    const uint32_t a = va[t] + g * 16 * ROWB;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLT_LDS s16x4*)(uintptr_t)a);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MLT_LDS s16x4*)(uintptr_t)(a + 8 * ROWB));
+    f = join_tr<V8>(lo, hi);
+  };
+  auto read_k_frag = [&](int fi, V8& f) __attribute__((always_inline)) {
+    const uint32_t a = ka[fi >> 1] + (fi & 1) * 32 * ROWB;
+    f = __builtin_bit_cast(V8, *(const MLT_LDS u32x4*)(uintptr_t)a);
+  };
+  auto mfma_v = [&](int g, int t, const V8& f) __attribute__((always_inline)) {
+    o_acc[t] = mfma32(f, __builtin_bit_cast(V8, pq[g]), o_acc[t]);
+  };
+  auto mfma_k = [&](int fi, const V8& f) __attribute__((always_inline)) {
+    if (fi < 2) {
+      f32x16 z;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) z[r] = 0.f;
+      s_acc[fi & 1] = mfma32(f, __builtin_bit_cast(V8, qf[fi >> 1]), z);
+    } else {
+      s_acc[fi & 1] = mfma32(f, __builtin_bit_cast(V8, qf[fi >> 1]), s_acc[fi & 1]);
+    }
+  };
+#define MLT_SB() __builtin_amdgcn_sched_barrier(0)
+
+  // ---- softmax of S_j (in s_acc) -> pq, mc_run, rescaled o_acc and l_run (mha_pp_kernel's, without
+  // the causal part)
+  auto softmax_tile = [&](int j) __attribute__((always_inline)) {
+    const int kb0 = j * PA_BN;
+    if (kb0 + PA_BN > Sk) {
+      const int rel = Sk - 1 - (kb0 + 4 * h);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (32 * kb + 8 * (r >> 2) + (r & 3) > rel) s_acc[kb][r] = -__builtin_inff();
+    }
+    float mx = max3(s_acc[0][0], s_acc[0][1], s_acc[0][2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) mx = max3(mx, s_acc[0][r], s_acc[0][r + 1]);
+    mx = max3(mx, s_acc[0][15], s_acc[1][0]);
+#pragma unroll
+    for (int r = 1; r < 15; r += 2) mx = max3(mx, s_acc[1][r], s_acc[1][r + 1]);
+    mx = __builtin_fmaxf(mx, s_acc[1][15]);
+    mx = both_halves_max(mx);
+    const float t = mx * c;
+    const bool grow = t - mc_run > PA_LAZY_T;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+      const float mc_new = grow ? t : mc_run;
+      const float alpha = grow ? __builtin_amdgcn_exp2f(mc_run - t) : 1.f;
+      l_run *= alpha;
+#pragma unroll
+      for (int tt = 0; tt < NDT; ++tt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_acc[tt][r] *= alpha;
+      mc_run = mc_new;
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r], c, -mc_run));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s_acc[kb][r + 1], c, -mc_run));
+        pq[2 * kb + r / 8][(r / 2) & 3] = Elem<Tag>::pack2(p0, p1);
+      }
+  };
+
+  // ---- O = O^T / l for the item whose accumulators are complete, then a clean start for the next
+  auto store_item = [&](int bh_, int q0_) __attribute__((always_inline)) {
+    const int my_q_ = q0_ + lq;
+    const float l_tot = both_halves_sum(l_run);
+    const float inv = 1.f / l_tot;
+    if (my_q_ < Sq) {
+      uint16_t* op = O + ((int64_t)bh_ * Sq + my_q_) * D + 4 * h;
+#pragma unroll
+      for (int t = 0; t < NDT; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 w;
+          w[0] = Elem<Tag>::pack2(o_acc[t][4 * g] * inv, o_acc[t][4 * g + 1] * inv);
+          w[1] = Elem<Tag>::pack2(o_acc[t][4 * g + 2] * inv, o_acc[t][4 * g + 3] * inv);
+          *reinterpret_cast<u32x2_mem*>(op + t * 32 + 8 * g) = w;
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[t][r] = 0.f;
+    l_run = 0.f;
+    mc_run = -__builtin_inff();
+  };
+
+  // s_waitcnt vmcnt(n) lgkmcnt(LG) for a wavefront-uniform n from the set the schedule produces
+  // (multiples of LPT plus NQL or NST); anything else waits for everything.
+  auto wait_vm0 = [&](int n) __attribute__((always_inline)) {     // with lgkmcnt(0)
+    switch (n) {
+#define MLT_W(N) case N: __builtin_amdgcn_s_waitcnt(wait_imm(N, 0)); break;
+      MLT_W(2) MLT_W(4) MLT_W(6) MLT_W(8) MLT_W(10) MLT_W(12) MLT_W(14) MLT_W(16) MLT_W(18) MLT_W(20) MLT_W(22) MLT_W(24) MLT_W(26) MLT_W(28) MLT_W(30) MLT_W(32)
+#undef MLT_W
+      default: __builtin_amdgcn_s_waitcnt(wait_imm(0, 0)); break;
+    }
+  };
+  auto wait_vm15 = [&](int n) __attribute__((always_inline)) {    // LDS counter left alone
+    switch (n) {
+#define MLT_W(N) case N: __builtin_amdgcn_s_waitcnt(wait_imm(N, 15)); break;
+      MLT_W(2) MLT_W(4) MLT_W(6) MLT_W(8) MLT_W(10) MLT_W(12) MLT_W(14) MLT_W(16) MLT_W(18) MLT_W(20) MLT_W(22) MLT_W(24) MLT_W(26) MLT_W(28) MLT_W(30) MLT_W(32)
+#undef MLT_W
+      default: __builtin_amdgcn_s_waitcnt(wait_imm(0, 15)); break;
+    }
+  };
+
+  // ---- start of the stream: Q of the first item, the first tiles, S_0 (as in mha_pp_kernel)
+  int item = (int)blockIdx.x;                 // the item being computed
+  int bh, qt;
+  block_map(item, total, nq, bh, qt);
+  int q0 = qt * PA_BM + wave * 32;
+  int o_bh = bh, o_q0 = q0;                   // the item the accumulators belong to
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) qf[kk] = u32x4{0u, 0u, 0u, 0u};
+  q_issue(bh, q0);
+#pragma unroll
+  for (int t = 0; t < PA_AHEAD; ++t) issue_next();
+  if (NT >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 15));
+  else __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));     // NT >= 2
+  __builtin_amdgcn_s_barrier();
+  if (grp == 1) __builtin_amdgcn_s_barrier();            // stagger: group 1 runs one phase behind
+  q_finish();
+  {
+#pragma unroll
+    for (int i = 0; i < NDT; ++i) read_k_frag(i, fb[0][i]);
+#pragma unroll
+    for (int i = 0; i < NDT; ++i) read_k_frag(NDT + i, fb[1][i]);
+    MLT_SB();
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+      for (int i = 0; i < NDT; ++i) {
+        mfma_k(ch * NDT + i, fb[ch & 1][i]);
+        MLT_SB();
+        if (ch < 2) read_k_frag((ch + 2) * NDT + i, fb[ch & 1][i]);
+        else read_v_frag(ch - 2, i, fb[ch & 1][i]);
+        MLT_SB();
+      }
+    if (grp == 1) {
+      if (NT >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+      else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+    }
+    __builtin_amdgcn_s_barrier();
+  }
+
+  // ---- the stream of key tiles: softmax phase X, compute phase C per tile. j is the tile's number
+  // inside its item, g its number in the stream.
+  int slot_off = 0;           // ring offset of the current tile's slot
+  int st_age = 8;             // tiles since this wavefront last issued O stores (0: in this tile)
+  int j = 0;
+  for (int g = 0; g < NT; ++g) {
+    const int slot_off_next = slot_off + L::SLOT_B == L::SMEM ? 0 : slot_off + L::SLOT_B;
+    const bool more = g + 1 < NT;                        // S of stream tile g+1 is wanted
+    const bool first = j == 0 && g > 0;                  // an item ended with the previous tile
+    const bool last = j == nblk - 1 && more;             // another item follows this tile
+    // ---- X: Q of the next item (at an item's last tile), stream tile g+3 into the slot of tile
+    // g-2, the finished O tile (at an item's first tile), then the softmax of S_g
+    if (last) {
+      item += G;
+      block_map(item, total, nq, bh, qt);
+      q0 = qt * PA_BM + wave * 32;
+      q_issue(bh, q0);
+    }
+    issue_next();
+    MLT_SB();
+    if (first) {
+      if (o_q0 < Sq) st_age = 0;       // some lane of this wavefront has a row to store
+      store_item(o_bh, o_q0);
+      o_bh = bh; o_q0 = q0;
+    }
+    MLT_SB();
+    softmax_tile(j);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(pq[i]));
+    MLT_SB();
+    if (grp == 0) {
+      // needed: tile g+1. Issued after it: tiles g+2, g+3 (those that exist), the O stores of this
+      // or the last two tiles' softmax phases, this phase's Q loads.
+      int n = ((g + 3 < NT ? 1 : 0) + (g + 2 < NT ? 1 : 0)) * LPT;
+      if (st_age <= 2) n += NST;
+      if (last) n += NQL;
+      wait_vm0(n);
+    } else {
+      __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
+    }
+    __builtin_amdgcn_s_barrier();
+    MLT_SB();
+    if (D == 128) __builtin_amdgcn_s_setprio(1);
+    // ---- C: O^T += V_g^T P_g^T, then S^T of stream tile g+1 (after the last tile of an item that
+    // is K_0 of the next item against the next item's Q), then the first two V groups of tile g+1
+    {
+      const uint32_t dslot = (uint32_t)(slot_off_next - slot_off);
+#pragma unroll
+      for (int gi = 0; gi < 4; ++gi)
+#pragma unroll
+        for (int t = 0; t < NDT; ++t) {
+          mfma_v(gi, t, fb[gi & 1][t]);
+          MLT_SB();
+          if (gi < 2) read_v_frag(gi + 2, t, fb[gi & 1][t]);
+          else read_k_frag((gi - 2) * NDT + t, fb[gi & 1][t]);
+          if (gi == 0) { ka[2 * t] += dslot; ka[2 * t + 1] += dslot; }
+          if (gi == 3) va[t] += dslot;
+          MLT_SB();
+        }
+      if (last) {
+        // the Q loads were issued before stream tile g+3 (if there is one)
+        if (g + 3 < NT) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+        else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+        q_finish();
+        MLT_SB();
+      }
+      if (more) {
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch)
+#pragma unroll
+          for (int i = 0; i < NDT; ++i) {
+            mfma_k(ch * NDT + i, fb[ch & 1][i]);
+            MLT_SB();
+            if (ch < 2) read_k_frag((ch + 2) * NDT + i, fb[ch & 1][i]);
+            else read_v_frag(ch - 2, i, fb[ch & 1][i]);
+            MLT_SB();
+          }
+      }
+#pragma unroll
+      for (int gi = 0; gi < 4; ++gi)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) l_run = Elem<Tag>::add_pair(pq[gi][e], l_run);
+      asm volatile("" : "+v"(l_run));
+    }
+    if (D == 128) __builtin_amdgcn_s_setprio(0);
+    MLT_SB();
+    if (grp == 1) {
+      // needed: tile g+2. Issued after it: tile g+3 (if it exists) and the O stores of this tile's
+      // or the previous tile's softmax phase.
+      int n = g + 3 < NT ? LPT : 0;
+      if (st_age <= 1) n += NST;
+      wait_vm15(n);
+    }
+    __builtin_amdgcn_s_barrier();
+    MLT_SB();
+    slot_off = slot_off_next;
+    ++st_age;
+    j = j + 1 == nblk ? 0 : j + 1;
+  }
+#undef MLT_SB
+  if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
+  store_item(o_bh, o_q0);
+}
+
+// ---------------------------------------------------------------------------------------------
 // The same kernel on 16x16x32 MFMAs. Schedule, LDS ring, swizzles, loads and softmax are those of
 // mha_pp_kernel above; what changes is the shape of the hardware dot and with it who holds what.
 // Measured on N(0,1) operands the chip sustains 2100 TFLOP/s of 16x16x32 bf16 MFMAs against 1850
@@ -860,6 +1270,44 @@ int launch_mha_pp(const MhaArgs& a, hipStream_t s) {
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
+// The persistent kernel: one workgroup per CU (two for D = 64, which leaves room for them), at
+// most one per item.
+template <typename Tag, int D>
+int launch_mha_ps(const MhaArgs& a, hipStream_t s) {
+  typedef PaCfg<D> L;
+  auto kern = mha_ps_kernel<Tag, D>;
+  static thread_local int configured_dev = -1;          // opt in to > 64 KB LDS once per device
+  static thread_local int ncu = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
+  if (configured_dev != dev) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            L::SMEM) != hipSuccess ||
+        hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        ncu <= 0) {
+      (void)hipGetLastError();
+      return MLT_ERR_LAUNCH;
+    }
+    configured_dev = dev;
+  }
+  const int nq = (int)((a.Sq + PA_BM - 1) / PA_BM);
+  const int64_t total = a.B * a.H * nq;
+  int64_t slots = (int64_t)ncu * (D == 64 ? 2 : 1);
+  // Tuning/test override: MLT_MHA_PS_GRID = number of workgroups (small values make every
+  // workgroup walk through many items even on a small problem).
+  if (const char* e = getenv("MLT_MHA_PS_GRID")) {
+    const long v = strtol(e, nullptr, 10);
+    if (v >= 1 && v < slots) slots = v;
+  }
+  const unsigned grid = (unsigned)(total < slots ? total : slots);
+  const float LOG2E = 1.4426950408889634f;
+  float c = (a.scale < 0 ? -a.scale : a.scale) * LOG2E;   // c > 0 always, as in launch_mha_pp
+  if (c < 1e-30f) c = 1e-30f;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(PA_NT), L::SMEM, s, a.Q, a.K, a.V, a.O,
+                     (int)a.Sq, (int)a.Sk, nq, (int)total, c, a.scale < 0 ? 1 : 0);
+  return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
+}
+
 template <typename Tag, int MS>
 int run_mha_pp_t(const MhaArgs& a, hipStream_t s) {
   if (a.D == 128) return a.causal ? launch_mha_pp<Tag, 128, true, MS>(a, s) : launch_mha_pp<Tag, 128, false, MS>(a, s);
@@ -871,6 +1319,21 @@ int run_mha_pp_t(const MhaArgs& a, hipStream_t s) {
 
 // Sk * D * 2 must fit the 32-bit per-lane byte offsets of the direct loads.
 bool mha_pp_ok(const MhaArgs& a) { return (a.D == 64 || a.D == 128) && a.Sk * a.D * 2 < ((int64_t)1 << 31); }
+
+// The persistent kernel takes the unmasked case with at least two key tiles per item; the item
+// and stream-tile counters are 32-bit.
+bool mha_ps_ok(const MhaArgs& a) {
+  if (!mha_pp_ok(a) || a.causal || a.Sk <= PA_BN || a.Sq < 1 || a.B * a.H < 1) return false;
+  const int64_t nq = (a.Sq + PA_BM - 1) / PA_BM, nblk = (a.Sk + PA_BN - 1) / PA_BN;
+  const int64_t total = a.B * a.H * nq;
+  return total < ((int64_t)1 << 30) && total * nblk < ((int64_t)1 << 30);
+}
+
+int run_mha_ps(const MhaArgs& a, hipStream_t s) {
+  if (!mha_ps_ok(a)) return MLT_ERR_UNSUPPORTED;
+  if (a.D == 128) return a.dtype == MLT_BF16 ? launch_mha_ps<bf16_tag, 128>(a, s) : launch_mha_ps<f16_tag, 128>(a, s);
+  return a.dtype == MLT_BF16 ? launch_mha_ps<bf16_tag, 64>(a, s) : launch_mha_ps<f16_tag, 64>(a, s);
+}
 
 int run_mha_pp(const MhaArgs& a, int mfma_size, hipStream_t s) {
   if (mfma_size == 16)

@@ -68,9 +68,12 @@ struct MhaPlan {
   bool supported = false;
   bool two_group = false;   // mha_pp.hip (default) or the single-schedule kernel of mha.hip
   int mfma_size = 32;       // two-group kernel: 32 = 32x32x16 MFMAs, 16 = 16x16x32
+  bool persistent = false;  // two-group kernel, one workgroup per CU walking through the items
 };
 bool mha_pp_ok(const MhaArgs& a);
 int run_mha_pp(const MhaArgs& a, int mfma_size, hipStream_t s);
+bool mha_ps_ok(const MhaArgs& a);              // mha_pp.hip: can the persistent kernel take this problem?
+int run_mha_ps(const MhaArgs& a, hipStream_t s);
 
 // probe.hip: launches the register-only MFMA loop, returns the flop it will execute (< 0: launch failed)
 double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, int mfma_size, hipStream_t s);

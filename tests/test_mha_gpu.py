@@ -18,8 +18,10 @@ BF16, FP16 = inputs.BF16, inputs.FP16
 def _announce(request):
     print("\n[case] %s" % request.node.name, flush=True)
     os.environ.pop("MLT_MHA_VARIANT", None)
+    os.environ.pop("MLT_MHA_PS_GRID", None)
     yield
     os.environ.pop("MLT_MHA_VARIANT", None)
+    os.environ.pop("MLT_MHA_PS_GRID", None)
 
 
 def _go(B, H, Sq, Sk, D, dtype, causal, seed=0, scale=None, q_gain=1.0, **kw):
@@ -42,7 +44,7 @@ def test_small_multi_tile(dtype, causal, D):
     assert st["rel_rms"] < (1.5e-2 if dtype == BF16 else 2e-3)
 
 
-@pytest.mark.parametrize("variant,suffix", [("pp16", "_pp16"), ("pp32", "_pp"), ("single", "256x64")])
+@pytest.mark.parametrize("variant,suffix", [("pp16", "_pp16"), ("pp32", "_pp"), ("single", "256x64"), ("ps", "")])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("D,dtype", [(128, BF16), (64, FP16), (128, FP16), (64, BF16)])
 def test_every_kernel_variant(variant, suffix, causal, D, dtype):
@@ -55,6 +57,35 @@ def test_every_kernel_variant(variant, suffix, causal, D, dtype):
     assert binding.mlt_last_kernel().endswith(suffix)
     _go(2, 1, 300, 300, D, dtype, causal, seed=12, q_gain=3.0)
     assert binding.mlt_last_kernel().endswith(suffix)
+
+
+@pytest.mark.parametrize("grid", [1, 3, 8, 0])
+@pytest.mark.parametrize("D,dtype", [(128, BF16), (64, FP16), (128, FP16), (64, BF16)])
+def test_persistent_kernel_walks_items(grid, D, dtype):
+    """The unmasked case runs in the persistent kernel: every workgroup walks through several
+    (head, query tile) items as one stream of key tiles. Few workgroups (the grid override) make
+    each of them cross many item boundaries: 2 to 7 key tiles per item, ragged key and query ends
+    (the last query tile of (3, 5, 300, .) leaves wavefronts without any row), a negative scale,
+    peaky rows."""
+    from paper_2503_14985_amd import binding
+    os.environ["MLT_MHA_VARIANT"] = "ps"
+    if grid:
+        os.environ["MLT_MHA_PS_GRID"] = str(grid)
+    for (B, H, Sq, Sk, kw) in [(3, 5, 300, 200, {}), (1, 7, 700, 128, {}), (2, 3, 512, 435, {"q_gain": 3.0}),
+                               (1, 9, 256, 100, {"scale": -0.11}), (1, 2, 1100, 65, {})]:
+        _go(B, H, Sq, Sk, D, dtype, False, seed=31 + Sk, **kw)
+        assert binding.mlt_last_kernel().endswith("_ps")
+    # one key tile per item, and every masked problem, stay with the per-item kernel
+    _go(1, 2, 300, 64, D, dtype, False, seed=5)
+    assert binding.mlt_last_kernel().endswith("_pp")
+    _go(1, 2, 300, 200, D, dtype, True, seed=6)
+    assert binding.mlt_last_kernel().endswith("_pp")
+    # default routing: D = 128 with at most 16 key tiles per item
+    os.environ.pop("MLT_MHA_VARIANT", None)
+    _go(1, 2, 300, 200, D, dtype, False, seed=7)
+    assert binding.mlt_last_kernel().endswith("_ps" if D == 128 else "_pp")
+    _go(1, 1, 256, 1100, D, dtype, False, seed=8)
+    assert binding.mlt_last_kernel().endswith("_pp")
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1, 1), (1, 1, 7, 1), (1, 3, 33, 17), (2, 2, 300, 200),
