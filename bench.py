@@ -189,6 +189,94 @@ def mfma_ceiling(binding, ev, A, dev):
     return res
 
 
+class PowerSampler:
+    """Board power from the amdgpu hwmon files (microwatts), sampled by a thread while kernels run.
+    With several cards in sysfs the one drawing the most is taken: it is the one being driven."""
+
+    def __init__(self):
+        import glob
+        self.inputs = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") or
+                             glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))
+        self.samples, self._stop, self._th = [], False, None
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return int(f.read().strip())
+        except (OSError, ValueError):
+            return None
+
+    def cap_w(self):
+        caps = [self._read(os.path.join(os.path.dirname(p), "power1_cap")) for p in self.inputs]
+        caps = [c for c in caps if c]
+        return max(caps) / 1e6 if caps else None
+
+    def _poll(self):
+        while not self._stop:
+            vals = [v for v in (self._read(p) for p in self.inputs) if v is not None]
+            if vals:
+                self.samples.append((time.perf_counter(), max(vals) / 1e6))
+            time.sleep(0.02)
+
+    def start(self):
+        import threading
+        self.samples, self._stop = [], False
+        self._th = threading.Thread(target=self._poll, daemon=True)
+        self._th.start()
+
+    def stop(self, since):
+        self._stop = True
+        self._th.join()
+        w = [v for (t, v) in self.samples if t >= since]
+        return sum(w) / len(w) if w else None
+
+
+def power_context(binding, A, B, C, Q, K, V, O, scale):
+    """Why the fractions of the nominal peak are what they are: each of the two kernels launched
+    back to back for about 1.5 s, once on the benchmark's N(0,1) operands and once on all-zero
+    operands of the same shapes (same instructions, same memory traffic, no switching in the
+    multipliers), with the board power sampled meanwhile (second half of each run). On the N(0,1)
+    operands the board sits at its power cap and the clock is what the cap leaves; on zeros it does
+    not, and the rate is what the kernel's schedule reaches at full clock."""
+    import torch
+    ps = PowerSampler()
+    M, N, Kd = GEMM_MNK
+    Bq, H, Sq, Sk, D = MHA_SHAPE
+    f_gemm, f_mha = 2.0 * M * N * Kd, 4.0 * Bq * H * Sq * Sk * D
+    Az, Bz = torch.zeros_like(A), torch.zeros_like(B)
+    Qz, Kz, Vz = torch.zeros_like(Q), torch.zeros_like(K), torch.zeros_like(V)
+    runs = (("gemm_n01", lambda: binding.mlt_gemm(A, B, C=C), f_gemm),
+            ("gemm_zeros", lambda: binding.mlt_gemm(Az, Bz, C=C), f_gemm),
+            ("mha_n01", lambda: binding.mlt_mha_fwd(Q, K, V, scale, causal=False, O=O), f_mha),
+            ("mha_zeros", lambda: binding.mlt_mha_fwd(Qz, Kz, Vz, scale, causal=False, O=O), f_mha))
+    res = {"cap_w": ps.cap_w()}
+    secs = 1.5
+    for name, fn, flop in runs:
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        ps.start()
+        t0 = time.perf_counter()
+        n, t_half, n_half = 0, None, 0
+        while True:
+            for _ in range(25):
+                fn()
+            torch.cuda.synchronize()
+            n += 25
+            now = time.perf_counter()
+            if t_half is None and now - t0 >= secs / 2:
+                t_half, n_half = now, n
+            if now - t0 >= secs:
+                break
+        watts = ps.stop(t_half)
+        res[name] = {"tflops": flop * (n - n_half) / (now - t_half) / 1e12,
+                     "avg_w": None if watts is None else round(watts, 1)}
+    res["note"] = ("each kernel launched back to back for 1.5 s; rate and board power (hwmon "
+                   "power1_input) over the second half; zeros = all-zero operands of the same shapes")
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,7 +288,7 @@ def main():
                     help="run only one kernel (for counter runs of that kernel): one of the two of "
                          "the step, or the paged-attention decode kernel")
     ap.add_argument("--no-ceiling", action="store_true",
-                    help="skip the measurement of the power-limited MFMA ceiling")
+                    help="skip the context measurements (MFMA and HBM ceilings, paged decode, power)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps also run plain device copies of 256 MiB, so a "
                          "counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) can be scaled by "
@@ -320,6 +408,7 @@ def main():
         out["mfma_ceiling"] = mfma_ceiling(binding, ev, A, dev)
         out["paged_decode"] = paged_decode(binding, ev, dev)
         out["hbm_ceiling"] = hbm_ceiling(binding, ev, dev)
+        out["power"] = power_context(binding, A, B, C, Q, K, V, O, scale)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(A_h, B_h, Q_h, K_h, V_h, scale)
     print(json.dumps(out))
