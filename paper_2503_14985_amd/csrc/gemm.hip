@@ -434,9 +434,17 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
     return p;
   }
-  // Big tile when it still fills the chip, otherwise the small one.
+  // Big tile or small tile: whichever needs less time per K step over the whole grid. Measured per
+  // K step of 64 and per round of 256 workgroups (one per CU): two-group 256x256 kernel 1.17 us,
+  // older 256x256 kernel 1.8 us, 128x128 kernel with 8 wavefronts 0.6 us. (3072^3, 144 big tiles:
+  // 1033 TFLOP/s against 739 with 576 small ones; 2048^3, 64 big tiles: 437 against 758.)
+  constexpr int64_t NCU = 256;
   const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-  int v = tiles256 >= 192 ? (gemm_pp_ok(g) ? GEMM_256_PP16 : GEMM_256_W8) : GEMM_128;
+  const int64_t tiles128 = ((g.M + 127) / 128) * ((g.N + 127) / 128);
+  const bool pp = gemm_pp_ok(g);
+  const int64_t cost256 = ((tiles256 + NCU - 1) / NCU) * (pp ? 20 : 30);
+  const int64_t cost128 = ((tiles128 + NCU - 1) / NCU) * 10;
+  int v = cost256 <= cost128 ? (pp ? GEMM_256_PP16 : GEMM_256_W8) : GEMM_128_W8;
   if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS && g.forced != GEMM_SKINNY &&
       g.forced != GEMM_SKINNY_DMA && g.forced != GEMM_SKINNY_DMAW)
     v = g.forced;
@@ -461,6 +469,8 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       p.name = g.transB ? "gemm_nt_256x256x64_w2x4_pp16" : "gemm_nn_256x256x64_w2x4_pp16"; break;
     case GEMM_256_W4: p.bm = p.bn = 256; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x2_swp" : "gemm_nn_256x256x64_w2x2_swp"; break;
+    case GEMM_128_W8: p.bm = p.bn = 128; p.wm = 2; p.wn = 4;
+      p.name = g.transB ? "gemm_nt_128x128x64_w2x4" : "gemm_nn_128x128x64_w2x4"; break;
     default: p.bm = p.bn = 128; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_128x128x64_w2x2" : "gemm_nn_128x128x64_w2x2"; break;
   }
@@ -490,6 +500,7 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_256_W8X1: return launch_tile_tb<Tag, 256, 256, 64, 8, 1>(g, s);
     case GEMM_256_W1X8: return launch_tile_tb<Tag, 256, 256, 64, 1, 8>(g, s);
     case GEMM_128: return launch_tile_tb<Tag, 128, 128, 64, 2, 2>(g, s);
+    case GEMM_128_W8: return launch_tile_tb<Tag, 128, 128, 64, 2, 4>(g, s);
     case GEMM_256_PP: return run_gemm_pp(g, 32, s);
     case GEMM_256_PP16: return run_gemm_pp(g, 16, s);
     case GEMM_256_W4: return run_gemm_w4(g, s);

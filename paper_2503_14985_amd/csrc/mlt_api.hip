@@ -29,12 +29,13 @@ bool device_is_gfx950() {
 }
 
 int forced_gemm_variant() {
-  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 256w8 | 256w8t | 256pp | 256pp16 | 256w4 | skinny | skinnydma | skinnydmaw.
+  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 128w8 | 256w8 | 256w8t | 256pp | 256pp16 | 256w4 | skinny | skinnydma | skinnydmaw.
   const char* e = getenv("MLT_GEMM_VARIANT");
   if (!e || !*e) return GEMM_AUTO;
   if (!strcmp(e, "general")) return GEMM_GENERAL;
   if (!strcmp(e, "256")) return GEMM_256;
   if (!strcmp(e, "128")) return GEMM_128;
+  if (!strcmp(e, "128w8")) return GEMM_128_W8;
   if (!strcmp(e, "256w8")) return GEMM_256_W8;
   if (!strcmp(e, "256w8t")) return GEMM_256_W8T;
   if (!strcmp(e, "256pp")) return GEMM_256_PP;

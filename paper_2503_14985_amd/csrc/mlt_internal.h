@@ -20,6 +20,7 @@ enum GemmVariant {
   GEMM_256_PP16 = 11, // the two-group kernel on 16x16x32 MFMAs
   GEMM_256_W8X1 = 12, // 256x256x64, 8 wavefronts as 8x1: row strips of 32 x 256 ("horizontal")
   GEMM_256_W1X8 = 13, // 256x256x64, 8 wavefronts as 1x8: column strips of 256 x 32 ("vertical")
+  GEMM_128_W8 = 14,   // 128x128x64, 8 wavefronts (2x4) of 64x32
   GEMM_NUM_VARIANTS
 };
 

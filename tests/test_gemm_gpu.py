@@ -37,7 +37,7 @@ def test_config1_bf16_512_uniform():
     assert name.startswith("gemm_nn")
 
 
-@pytest.mark.parametrize("variant", ["256", "128", "general"])
+@pytest.mark.parametrize("variant", ["256", "128", "128w8", "general"])
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 def test_small_multi_tile_ragged(variant, transB, dtype):
@@ -45,7 +45,7 @@ def test_small_multi_tile_ragged(variant, transB, dtype):
     _go(520, 776, 328, dtype, transB, variant=variant, seed=1)
 
 
-@pytest.mark.parametrize("variant", ["256", "128"])
+@pytest.mark.parametrize("variant", ["256", "128", "128w8"])
 @pytest.mark.parametrize("transB", [False, True])
 def test_exact_tiles(variant, transB):
     _go(512, 768, 256, BF16, transB, variant=variant, seed=2)
@@ -114,6 +114,19 @@ def test_skinny_streaming_kernel_is_the_default_for_large_b():
     assert "skinny" in name and not name.endswith("_stream")
     name, _ = _go(40, 16384, 2048, FP16, True, std=0.02, seed=9)      # taller A: the 64-column form
     assert name == "gemm_nt_skinny_64cols_stream"
+
+
+@pytest.mark.parametrize("shape,tile", [((1024, 1024, 1024), "128x128x64_w2x4"), ((2048, 2048, 2048), "128x128x64_w2x4"),
+                                        ((3072, 3072, 3072), "256x256x64_w2x4_pp16"),
+                                        ((512, 8192, 1024), "128x128x64_w2x4"), ((1536, 4096, 512), "256x256x64_w2x4_pp16"),
+                                        ((2048, 2048, 2048 + 8), "128x128x64_w2x4")])
+def test_tile_size_routing(shape, tile):
+    """Big or small workgroup tile by the time per K step over the whole grid: the 256 x 256
+    two-group kernel once its tiles cover enough of the chip, the 128 x 128 kernel with eight
+    wavefronts below that; sampled parity at the real size either way."""
+    M, N, K = shape
+    name, _ = _go(M, N, K, BF16, False, seed=21)
+    assert name.endswith(tile), name
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (37, 53, 29), (65, 63, 33), (16, 8, 8), (8, 16, 24),
