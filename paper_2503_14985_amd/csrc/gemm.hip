@@ -434,17 +434,26 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
     return p;
   }
-  // Big tile or small tile: whichever needs less time per K step over the whole grid. Measured per
-  // K step of 64 and per round of 256 workgroups (one per CU): two-group 256x256 kernel 1.17 us,
-  // older 256x256 kernel 1.8 us, 128x128 kernel with 8 wavefronts 0.6 us. (3072^3, 144 big tiles:
-  // 1033 TFLOP/s against 739 with 576 small ones; 2048^3, 64 big tiles: 437 against 758.)
+  // Workgroup tile: the candidate that needs the least time per K step over the whole grid, i.e.
+  // (rounds of 256 workgroups, one per CU) x (its measured time per K step of 64): two-group
+  // 256x256 kernel 1.17 us, older 256x256 kernel 1.8 us, 128x128 with 8 wavefronts 0.57 us, 64x128
+  // 0.45 us, 64x64 0.41 us; ties go to the larger tile. (3072^3, 144 big tiles: 1033 TFLOP/s
+  // against 739 with 576 tiles of 128x128; 2048^3, 64 big tiles: 437 against 758; 256 x 4096 x
+  // 4096: 321 with 256 tiles of 64x64 against 236 with 64 tiles of 128x128.)
   constexpr int64_t NCU = 256;
-  const int64_t tiles256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-  const int64_t tiles128 = ((g.M + 127) / 128) * ((g.N + 127) / 128);
+  auto rounds = [&](int64_t bm, int64_t bn) {
+    const int64_t tiles = ((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
+    return (tiles + NCU - 1) / NCU;
+  };
   const bool pp = gemm_pp_ok(g);
-  const int64_t cost256 = ((tiles256 + NCU - 1) / NCU) * (pp ? 20 : 30);
-  const int64_t cost128 = ((tiles128 + NCU - 1) / NCU) * 10;
-  int v = cost256 <= cost128 ? (pp ? GEMM_256_PP16 : GEMM_256_W8) : GEMM_128_W8;
+  int v = pp ? GEMM_256_PP16 : GEMM_256_W8;
+  int64_t best = rounds(256, 256) * (pp ? 117 : 180);
+  const struct { int variant; int bm, bn; int64_t t; } small_tiles[] = {
+      {GEMM_128_W8, 128, 128, 57}, {GEMM_64X128_W8, 64, 128, 45}, {GEMM_64_W4, 64, 64, 41}};
+  for (const auto& c : small_tiles) {
+    const int64_t cost = rounds(c.bm, c.bn) * c.t;
+    if (cost < best) { best = cost; v = c.variant; }
+  }
   if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS && g.forced != GEMM_SKINNY &&
       g.forced != GEMM_SKINNY_DMA && g.forced != GEMM_SKINNY_DMAW)
     v = g.forced;
@@ -471,6 +480,10 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       p.name = g.transB ? "gemm_nt_256x256x64_w2x2_swp" : "gemm_nn_256x256x64_w2x2_swp"; break;
     case GEMM_128_W8: p.bm = p.bn = 128; p.wm = 2; p.wn = 4;
       p.name = g.transB ? "gemm_nt_128x128x64_w2x4" : "gemm_nn_128x128x64_w2x4"; break;
+    case GEMM_64X128_W8: p.bm = 64; p.bn = 128; p.wm = 2; p.wn = 4;
+      p.name = g.transB ? "gemm_nt_64x128x64_w2x4" : "gemm_nn_64x128x64_w2x4"; break;
+    case GEMM_64_W4: p.bm = p.bn = 64; p.wm = 2; p.wn = 2;
+      p.name = g.transB ? "gemm_nt_64x64x64_w2x2" : "gemm_nn_64x64x64_w2x2"; break;
     default: p.bm = p.bn = 128; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_128x128x64_w2x2" : "gemm_nn_128x128x64_w2x2"; break;
   }
@@ -501,6 +514,8 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_256_W1X8: return launch_tile_tb<Tag, 256, 256, 64, 1, 8>(g, s);
     case GEMM_128: return launch_tile_tb<Tag, 128, 128, 64, 2, 2>(g, s);
     case GEMM_128_W8: return launch_tile_tb<Tag, 128, 128, 64, 2, 4>(g, s);
+    case GEMM_64X128_W8: return launch_tile_tb<Tag, 64, 128, 64, 2, 4>(g, s);
+    case GEMM_64_W4: return launch_tile_tb<Tag, 64, 64, 64, 2, 2>(g, s);
     case GEMM_256_PP: return run_gemm_pp(g, 32, s);
     case GEMM_256_PP16: return run_gemm_pp(g, 16, s);
     case GEMM_256_W4: return run_gemm_w4(g, s);

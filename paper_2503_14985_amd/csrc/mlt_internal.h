@@ -21,6 +21,8 @@ enum GemmVariant {
   GEMM_256_W8X1 = 12, // 256x256x64, 8 wavefronts as 8x1: row strips of 32 x 256 ("horizontal")
   GEMM_256_W1X8 = 13, // 256x256x64, 8 wavefronts as 1x8: column strips of 256 x 32 ("vertical")
   GEMM_128_W8 = 14,   // 128x128x64, 8 wavefronts (2x4) of 64x32
+  GEMM_64X128_W8 = 15, // 64x128x64, 8 wavefronts (2x4) of 32x32
+  GEMM_64_W4 = 16,    // 64x64x64, 4 wavefronts (2x2) of 32x32
   GEMM_NUM_VARIANTS
 };
 

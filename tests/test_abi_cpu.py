@@ -119,8 +119,11 @@ def test_tiling_query_is_the_papers_partition_rule(binding):
     assert per_wave == [wg[0] // waves[0], wg[1] // waves[1]]
     # the hardware dot of the big-tile kernel is the 16x16x32 MFMA (the lower-power shape)
     assert mfma == [16, 16, 32] and per_wave[0] % 16 == 0 and per_wave[1] % 16 == 0
+    # small problems get smaller workgroup tiles, chosen by time per K step over the whole grid
     small = binding.mlt_query_tiling(0, (512, 512, 512, 1), 1)
-    assert small[0:2] == [128, 128]
+    assert small[0:2] == [64, 64] and small[2:4] == [2, 2] and small[4:6] == [32, 32]
+    mid = binding.mlt_query_tiling(0, (2048, 2048, 2048, 0), 0)
+    assert mid[0:2] == [128, 128] and mid[2:4] == [2, 4] and mid[4:6] == [64, 32]
     a = binding.mlt_query_tiling(1, (4096, 4096, 128, 0), 0)
     assert a[2:4] == [8, 1] and a[4] == a[0] // 8 and a[5] == 128 and a[9] == 64
     with pytest.raises(binding.MltError):

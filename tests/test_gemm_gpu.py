@@ -37,7 +37,7 @@ def test_config1_bf16_512_uniform():
     assert name.startswith("gemm_nn")
 
 
-@pytest.mark.parametrize("variant", ["256", "128", "128w8", "general"])
+@pytest.mark.parametrize("variant", ["256", "128", "128w8", "64x128", "64", "general"])
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 def test_small_multi_tile_ragged(variant, transB, dtype):
@@ -116,14 +116,15 @@ def test_skinny_streaming_kernel_is_the_default_for_large_b():
     assert name == "gemm_nt_skinny_64cols_stream"
 
 
-@pytest.mark.parametrize("shape,tile", [((1024, 1024, 1024), "128x128x64_w2x4"), ((2048, 2048, 2048), "128x128x64_w2x4"),
+@pytest.mark.parametrize("shape,tile", [((1024, 1024, 1024), "64x64x64_w2x2"), ((2048, 2048, 2048), "128x128x64_w2x4"),
                                         ((3072, 3072, 3072), "256x256x64_w2x4_pp16"),
-                                        ((512, 8192, 1024), "128x128x64_w2x4"), ((1536, 4096, 512), "256x256x64_w2x4_pp16"),
-                                        ((2048, 2048, 2048 + 8), "128x128x64_w2x4")])
+                                        ((512, 8192, 1024), "128x128x64_w2x4"), ((512, 4096, 1024), "64x128x64_w2x4"),
+                                        ((256, 4096, 2048), "64x64x64_w2x2"), ((2048, 2048, 2048 + 8), "128x128x64_w2x4"),
+                                        ((4096, 4096, 512), "256x256x64_w2x4_pp16")])
 def test_tile_size_routing(shape, tile):
-    """Big or small workgroup tile by the time per K step over the whole grid: the 256 x 256
-    two-group kernel once its tiles cover enough of the chip, the 128 x 128 kernel with eight
-    wavefronts below that; sampled parity at the real size either way."""
+    """The workgroup tile is the one with the least time per K step over the whole grid: the
+    256 x 256 two-group kernel once its tiles cover enough of the chip, 128 x 128, 64 x 128 or
+    64 x 64 below that; sampled parity at the real size either way."""
     M, N, K = shape
     name, _ = _go(M, N, K, BF16, False, seed=21)
     assert name.endswith(tile), name
