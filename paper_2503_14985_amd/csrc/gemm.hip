@@ -73,17 +73,23 @@ struct GemmTile {
   static_assert(BK % 16 == 0 && BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "MFMA tiling");
 };
 
-template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
+template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB, int KS>
+__global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
     int nbn, int epi, const uint16_t* __restrict__ bias) {
   typedef GemmTile<Tag, BM, BN, BK, WM, WN, TRANSB> Cfg;
   typedef typename Elem<Tag>::vec8 V8;
-  extern __shared__ __align__(16) char smem[];
+  extern __shared__ __align__(16) char smem_all[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // KS > 1: the workgroup holds KS groups of WM x WN wavefronts; group kg runs the whole pipeline
+  // below on its own LDS stages over its own share of the K steps, and the groups' accumulators
+  // are added through LDS at the end (see there). tid, wave: inside the group.
+  const int kg = KS == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / Cfg::NT);
+  const int tid = KS == 1 ? (int)threadIdx.x : (int)threadIdx.x % Cfg::NT;
+  const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
+  char* const smem = smem_all + kg * Cfg::SMEM;
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, nbm, nbn, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -220,8 +226,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
   const bool ragged_k = (K % BK) != 0;                  // only the last step can be partial
   constexpr int NKK = BK / 16;
   static_assert(NKK == 4, "the schedule below is written for four k slices per stage");
+  // This group's K steps: kt_begin .. kt_end-1 (all of them when KS == 1); every group runs the
+  // loop KTG times so that all wavefronts meet at the same barriers, idle once its steps are done.
+  const int KTG = (KT + KS - 1) / KS;
+  const int kt_begin = kg * KTG;
+  const int kt_end = kt_begin + KTG < KT ? kt_begin + KTG : KT;
+  auto load_tile = [&](int t) { load_global(t * BK, ragged_k && t == KT - 1); };
 
-  // Software pipeline. Stage s holds tile kt (s = kt & 1). During step kt:
+  // Software pipeline. Stage s holds the group's i-th tile (s = i & 1). During step kt:
   //   slice 0: read fragments of slice 1 | MFMAs of slice 0
   //   slice 1: read fragments of slice 2 | MFMAs of slice 1 | write tile kt+1 (already in
   //            registers since the previous step) to the other stage | issue the global loads
@@ -231,13 +243,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
   // The barrier sits where every wavefront has issued its last read of stage s and its writes
   // of tile kt+1, so after it stage s may be overwritten (in step kt+1) and tile kt+1 may be
   // read; its latency and that of the first fragment reads hide behind the MFMAs of slice 3.
-  load_global(0, ragged_k && KT == 1);
-  store_lds(0);
-  if (KT > 1) load_global(BK, ragged_k && KT == 2);
+  const bool any = kt_begin < kt_end;
+  if (any) {
+    load_tile(kt_begin);
+    store_lds(0);
+    if (kt_begin + 1 < kt_end) load_tile(kt_begin + 1);
+  }
   __syncthreads();
 
   V8 af[2][Cfg::TM], bf[2][Cfg::TN];
-  load_frags(smem, 0, af[0], bf[0]);
+  if (any) load_frags(smem, 0, af[0], bf[0]);
 
   auto mfma_slice = [&](int which) {
 #pragma unroll
@@ -247,37 +262,75 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_tile_kernel(
         acc[i][j] = mfma32(af[which][i], bf[which][j], acc[i][j]);
   };
 
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
+  for (int it = 0; it < KTG; ++it) {
+    const int kt = kt_begin + it;
+    const bool active = KS == 1 || kt < kt_end;
+    const int cur = it & 1;
     const char* st = smem + cur * Cfg::STAGE;
     const char* nx = smem + (cur ^ 1) * Cfg::STAGE;
-    const bool have_next = kt + 1 < KT;
+    const bool have_next = kt + 1 < kt_end;
 
-    load_frags(st, 1, af[1], bf[1]);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_slice(0);
-    __builtin_amdgcn_sched_barrier(0);
+    if (active) {
+      load_frags(st, 1, af[1], bf[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_slice(0);
+      __builtin_amdgcn_sched_barrier(0);
 
-    load_frags(st, 2, af[0], bf[0]);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_slice(1);
-    __builtin_amdgcn_sched_barrier(0);
-    if (have_next) {
-      store_lds(cur ^ 1);
-      if (kt + 2 < KT) load_global((kt + 2) * BK, ragged_k && kt + 3 == KT);
+      load_frags(st, 2, af[0], bf[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_slice(1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (have_next) {
+        store_lds(cur ^ 1);
+        if (kt + 2 < kt_end) load_tile(kt + 2);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+
+      load_frags(st, 3, af[1], bf[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_slice(0);                                    // slice 2 lives in fragment set 0
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-
-    load_frags(st, 3, af[1], bf[1]);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_slice(0);                                      // slice 2 lives in fragment set 0
-    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
 
-    if (have_next) load_frags(nx, 0, af[0], bf[0]);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_slice(1);                                      // slice 3 lives in fragment set 1
-    __builtin_amdgcn_sched_barrier(0);
+    if (active) {
+      if (have_next) load_frags(nx, 0, af[0], bf[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_slice(1);                                    // slice 3 lives in fragment set 1
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // ---- KS > 1: add the groups' accumulators. Groups 1 .. KS-1 park theirs in LDS (the stages
+  // are free now), register r of MFMA tile (i, j) of wavefront w at float index
+  // ((w*TM*TN + i*TN + j)*16 + r)*64 + lane of the group's area (consecutive lanes, consecutive
+  // words); group 0 adds them in the order 1, 2, ... and goes on to the epilogue alone.
+  if (KS > 1) {
+    static_assert(KS == 1 || (KS - 1) * BM * BN * 4 <= KS * Cfg::SMEM, "reduction area fits the stages");
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem_all);
+    const int mine = wave * Cfg::TM * Cfg::TN * 16 * 64 + lane;
+    if (kg > 0) {
+      float* dst = red + (kg - 1) * (BM * BN) + mine;
+#pragma unroll
+      for (int i = 0; i < Cfg::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Cfg::TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dst[((i * Cfg::TN + j) * 16 + r) * 64] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (kg > 0) return;
+#pragma unroll
+    for (int g2 = 1; g2 < KS; ++g2) {
+      const float* src = red + (g2 - 1) * (BM * BN) + mine;
+#pragma unroll
+      for (int i = 0; i < Cfg::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < Cfg::TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] += src[((i * Cfg::TN + j) * 16 + r) * 64];
+    }
   }
 
   // ---- epilogue: fp32 -> 16-bit (RNE), guarded element stores
@@ -365,23 +418,24 @@ __global__ void gemm_zero_kernel(int M, int N, uint16_t* __restrict__ C, int64_t
 // ------------------------------------------------------------------------------------------
 // Host side
 // ------------------------------------------------------------------------------------------
-template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB>
+template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB, int KS>
 static int launch_tile(const GemmArgs& g, hipStream_t s) {
   typedef GemmTile<Tag, BM, BN, BK, WM, WN, TRANSB> Cfg;
-  auto kern = gemm_tile_kernel<Tag, BM, BN, BK, WM, WN, TRANSB>;
+  static_assert(Cfg::NT * KS <= 1024 && KS * Cfg::SMEM <= 160 * 1024, "one workgroup, one CU's LDS");
+  auto kern = gemm_tile_kernel<Tag, BM, BN, BK, WM, WN, TRANSB, KS>;
   static thread_local int configured_dev = -1;          // opt in to > 64 KB LDS once per device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
   if (configured_dev != dev) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            Cfg::SMEM) != hipSuccess) {
+                            KS * Cfg::SMEM) != hipSuccess) {
       (void)hipGetLastError();
       return MLT_ERR_LAUNCH;
     }
     configured_dev = dev;
   }
   const int nbm = (int)((g.M + BM - 1) / BM), nbn = (int)((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(Cfg::NT), Cfg::SMEM, s, (int)g.M, (int)g.N,
+  hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(Cfg::NT * KS), KS * Cfg::SMEM, s, (int)g.M, (int)g.N,
                      (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.epi(), g.bias);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
@@ -436,10 +490,12 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   }
   // Workgroup tile: the candidate that needs the least time per K step over the whole grid, i.e.
   // (rounds of 256 workgroups, one per CU) x (its measured time per K step of 64): two-group
-  // 256x256 kernel 1.17 us, older 256x256 kernel 1.8 us, 128x128 with 8 wavefronts 0.57 us, 64x128
-  // 0.45 us, 64x64 0.41 us; ties go to the larger tile. (3072^3, 144 big tiles: 1033 TFLOP/s
-  // against 739 with 576 tiles of 128x128; 2048^3, 64 big tiles: 437 against 758; 256 x 4096 x
-  // 4096: 321 with 256 tiles of 64x64 against 236 with 64 tiles of 128x128.)
+  // 256x256 kernel 1.17 us, older 256x256 kernel 1.8 us; small tiles with the K steps split over
+  // 2 to 4 groups of wavefronts inside the workgroup: 128x128 0.575 us, 64x128 0.37 us, 64x64
+  // 0.22 us (unsplit, for K < 512: 0.60, 0.41, 0.35); ties go to the larger tile. (3072^3, 144
+  // big tiles: 1033 TFLOP/s against 739 with 576 tiles of 128x128; 2048^3, 64 big tiles: 437
+  // against 758; 256 x 4096 x 4096: 482 with 256 split tiles of 64x64, 326 unsplit, 244 with 64
+  // tiles of 128x128.)
   constexpr int64_t NCU = 256;
   auto rounds = [&](int64_t bm, int64_t bn) {
     const int64_t tiles = ((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
@@ -447,10 +503,11 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   };
   const bool pp = gemm_pp_ok(g);
   int v = pp ? GEMM_256_PP16 : GEMM_256_W8;
-  int64_t best = rounds(256, 256) * (pp ? 117 : 180);
-  const struct { int variant; int bm, bn; int64_t t; } small_tiles[] = {
-      {GEMM_128_W8, 128, 128, 57}, {GEMM_64X128_W8, 64, 128, 45}, {GEMM_64_W4, 64, 64, 41}};
-  for (const auto& c : small_tiles) {
+  int64_t best = rounds(256, 256) * (pp ? 1170 : 1800);
+  struct Cand { int variant; int bm, bn; int64_t t; };
+  const Cand split[] = {{GEMM_128_K2, 128, 128, 575}, {GEMM_64X128_K2, 64, 128, 370}, {GEMM_64_K4, 64, 64, 220}};
+  const Cand whole[] = {{GEMM_128_W8, 128, 128, 600}, {GEMM_64X128_W8, 64, 128, 410}, {GEMM_64_W4, 64, 64, 350}};
+  for (const auto& c : g.K >= 512 ? split : whole) {
     const int64_t cost = rounds(c.bm, c.bn) * c.t;
     if (cost < best) { best = cost; v = c.variant; }
   }
@@ -484,16 +541,24 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       p.name = g.transB ? "gemm_nt_64x128x64_w2x4" : "gemm_nn_64x128x64_w2x4"; break;
     case GEMM_64_W4: p.bm = p.bn = 64; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_64x64x64_w2x2" : "gemm_nn_64x64x64_w2x2"; break;
+    case GEMM_128_K2: p.bm = p.bn = 128; p.wm = 2; p.wn = 4;
+      p.name = g.transB ? "gemm_nt_128x128x64_w2x4_k2" : "gemm_nn_128x128x64_w2x4_k2"; break;
+    case GEMM_64X128_K2: p.bm = 64; p.bn = 128; p.wm = 2; p.wn = 4;
+      p.name = g.transB ? "gemm_nt_64x128x64_w2x4_k2" : "gemm_nn_64x128x64_w2x4_k2"; break;
+    case GEMM_64_K4: p.bm = p.bn = 64; p.wm = 2; p.wn = 2;
+      p.name = g.transB ? "gemm_nt_64x64x64_w2x2_k4" : "gemm_nn_64x64x64_w2x2_k4"; break;
     default: p.bm = p.bn = 128; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_128x128x64_w2x2" : "gemm_nn_128x128x64_w2x2"; break;
   }
   return p;
 }
 
-template <typename Tag, int BM, int BN, int BK, int WM, int WN>
+// KS: K-split groups per workgroup when B is stored N x K, KS_NN when it is stored K x N (whose
+// padded stage is larger, so fewer groups fit the LDS).
+template <typename Tag, int BM, int BN, int BK, int WM, int WN, int KS = 1, int KS_NN = KS>
 static int launch_tile_tb(const GemmArgs& g, hipStream_t s) {
-  return g.transB ? launch_tile<Tag, BM, BN, BK, WM, WN, true>(g, s)
-                  : launch_tile<Tag, BM, BN, BK, WM, WN, false>(g, s);
+  return g.transB ? launch_tile<Tag, BM, BN, BK, WM, WN, true, KS>(g, s)
+                  : launch_tile<Tag, BM, BN, BK, WM, WN, false, KS_NN>(g, s);
 }
 
 template <typename Tag>
@@ -516,6 +581,9 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_128_W8: return launch_tile_tb<Tag, 128, 128, 64, 2, 4>(g, s);
     case GEMM_64X128_W8: return launch_tile_tb<Tag, 64, 128, 64, 2, 4>(g, s);
     case GEMM_64_W4: return launch_tile_tb<Tag, 64, 64, 64, 2, 2>(g, s);
+    case GEMM_128_K2: return launch_tile_tb<Tag, 128, 128, 64, 2, 4, 2>(g, s);
+    case GEMM_64X128_K2: return launch_tile_tb<Tag, 64, 128, 64, 2, 4, 2>(g, s);
+    case GEMM_64_K4: return launch_tile_tb<Tag, 64, 64, 64, 2, 2, 4, 3>(g, s);
     case GEMM_256_PP: return run_gemm_pp(g, 32, s);
     case GEMM_256_PP16: return run_gemm_pp(g, 16, s);
     case GEMM_256_W4: return run_gemm_w4(g, s);

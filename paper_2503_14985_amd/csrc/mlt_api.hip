@@ -38,6 +38,9 @@ int forced_gemm_variant() {
   if (!strcmp(e, "128w8")) return GEMM_128_W8;
   if (!strcmp(e, "64x128")) return GEMM_64X128_W8;
   if (!strcmp(e, "64")) return GEMM_64_W4;
+  if (!strcmp(e, "128k2")) return GEMM_128_K2;
+  if (!strcmp(e, "64x128k2")) return GEMM_64X128_K2;
+  if (!strcmp(e, "64k4")) return GEMM_64_K4;
   if (!strcmp(e, "256w8")) return GEMM_256_W8;
   if (!strcmp(e, "256w8t")) return GEMM_256_W8T;
   if (!strcmp(e, "256pp")) return GEMM_256_PP;

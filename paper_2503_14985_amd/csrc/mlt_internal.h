@@ -23,6 +23,9 @@ enum GemmVariant {
   GEMM_128_W8 = 14,   // 128x128x64, 8 wavefronts (2x4) of 64x32
   GEMM_64X128_W8 = 15, // 64x128x64, 8 wavefronts (2x4) of 32x32
   GEMM_64_W4 = 16,    // 64x64x64, 4 wavefronts (2x2) of 32x32
+  GEMM_128_K2 = 17,   // 128x128x64, 2 groups of 8 wavefronts, each group half of the K steps
+  GEMM_64X128_K2 = 18, // 64x128x64, 2 groups of 8 wavefronts
+  GEMM_64_K4 = 19,    // 64x64x64, 4 groups of 4 wavefronts (3 when B is K x N), each group its share of the K steps
   GEMM_NUM_VARIANTS
 };
 

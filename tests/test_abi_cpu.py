@@ -121,7 +121,7 @@ def test_tiling_query_is_the_papers_partition_rule(binding):
     assert mfma == [16, 16, 32] and per_wave[0] % 16 == 0 and per_wave[1] % 16 == 0
     # small problems get smaller workgroup tiles, chosen by time per K step over the whole grid
     small = binding.mlt_query_tiling(0, (512, 512, 512, 1), 1)
-    assert small[0:2] == [64, 64] and small[2:4] == [2, 2] and small[4:6] == [32, 32]
+    assert small[0:2] == [64, 64] and small[2:4] == [2, 2] and small[4:6] == [32, 32]   # (x 4 K groups)
     mid = binding.mlt_query_tiling(0, (2048, 2048, 2048, 0), 0)
     assert mid[0:2] == [128, 128] and mid[2:4] == [2, 4] and mid[4:6] == [64, 32]
     a = binding.mlt_query_tiling(1, (4096, 4096, 128, 0), 0)

@@ -37,7 +37,7 @@ def test_config1_bf16_512_uniform():
     assert name.startswith("gemm_nn")
 
 
-@pytest.mark.parametrize("variant", ["256", "128", "128w8", "64x128", "64", "general"])
+@pytest.mark.parametrize("variant", ["256", "128", "128w8", "64x128", "64", "128k2", "64x128k2", "64k4", "general"])
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 def test_small_multi_tile_ragged(variant, transB, dtype):
@@ -116,11 +116,24 @@ def test_skinny_streaming_kernel_is_the_default_for_large_b():
     assert name == "gemm_nt_skinny_64cols_stream"
 
 
-@pytest.mark.parametrize("shape,tile", [((1024, 1024, 1024), "64x64x64_w2x2"), ((2048, 2048, 2048), "128x128x64_w2x4"),
+@pytest.mark.parametrize("variant", ["128k2", "64x128k2", "64k4"])
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("K", [8, 64, 72, 128, 200, 64 * 5, 64 * 9 + 24, 2048])
+def test_k_split_inside_the_workgroup(variant, transB, K):
+    """The small-tile kernels with 2 to 4 groups of wavefronts per workgroup, each group on its own
+    share of the K steps, summed through LDS: fewer K steps than groups (idle groups), uneven
+    shares, a partial last step, many steps; ragged M and N."""
+    for dtype in (BF16, FP16):
+        name, _ = _go(200, 328, K, dtype, transB, variant=variant, seed=40 + K % 7)
+        assert "_k" in name
+
+
+@pytest.mark.parametrize("shape,tile", [((1024, 1024, 1024), "64x64x64_w2x2_k4"), ((2048, 2048, 2048), "128x128x64_w2x4_k2"),
                                         ((3072, 3072, 3072), "256x256x64_w2x4_pp16"),
-                                        ((512, 8192, 1024), "128x128x64_w2x4"), ((512, 4096, 1024), "64x128x64_w2x4"),
-                                        ((256, 4096, 2048), "64x64x64_w2x2"), ((2048, 2048, 2048 + 8), "128x128x64_w2x4"),
-                                        ((4096, 4096, 512), "256x256x64_w2x4_pp16")])
+                                        ((512, 8192, 1024), "128x128x64_w2x4_k2"), ((512, 4096, 1024), "64x128x64_w2x4_k2"),
+                                        ((256, 4096, 2048), "64x64x64_w2x2_k4"), ((2048, 2048, 2048 + 8), "128x128x64_w2x4_k2"),
+                                        ((4096, 4096, 512), "256x256x64_w2x4_pp16"), ((1024, 1024, 256), "64x64x64_w2x2"),
+                                        ((2048, 2048, 448), "128x128x64_w2x4")])
 def test_tile_size_routing(shape, tile):
     """The workgroup tile is the one with the least time per K step over the whole grid: the
     256 x 256 two-group kernel once its tiles cover enough of the chip, 128 x 128, 64 x 128 or
