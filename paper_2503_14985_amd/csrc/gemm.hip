@@ -466,13 +466,17 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.bm = 64; p.bn = 64; p.bk = 32; p.wm = 2; p.wn = 2;
     return p;
   }
-  // Streaming variants (B through an LDS ring): worth it once B is well beyond the caches. One
-  // 16-row tile of A: 16 columns x 512 k per stage (the better HBM request shape); taller A: 64
-  // columns x 128 k (every A fragment, re-read from L2 per column block, serves four column
-  // tiles), provided 64-column blocks still fill the chip.
-  const bool stream_auto = g.forced == GEMM_AUTO && g.N * g.K >= ((int64_t)1 << 25);
-  const bool want_wide = g.forced == GEMM_SKINNY_DMAW || (stream_auto && g.M > 16 && g.N >= 16384);
-  const bool want_narrow = g.forced == GEMM_SKINNY_DMA || (stream_auto && !want_wide && g.M <= 16);
+  // Skinny kernels (B stored N x K, no LDS staging of A): the automatic choice for one 16-row
+  // tile of A, streaming B through an LDS ring (16 columns x 512 k per stage) once B is well
+  // beyond the caches, and for two row tiles against a small B. Taller A goes to the tile kernels
+  // below: from two row tiles on they are faster (64 x 28672 x 8192: 102 us against 140 us for
+  // the 64-column streaming form, 64 x 14336 x 4096: 20 us against 79 us), because the skinny
+  // kernels re-read A from L2 for every 16 or 64 columns. The 64-column streaming form stays
+  // selectable (MLT_GEMM_VARIANT=skinnydmaw).
+  const bool big_b = g.N * g.K >= ((int64_t)1 << 25);
+  const bool skinny_auto = g.forced == GEMM_AUTO && (g.M <= 16 || (g.M <= 32 && !big_b));
+  const bool want_wide = g.forced == GEMM_SKINNY_DMAW;
+  const bool want_narrow = g.forced == GEMM_SKINNY_DMA || (skinny_auto && big_b && g.M <= 16);
   if ((want_wide || want_narrow) && gemm_skinny_dma_ok(g)) {
     p.variant = want_wide ? GEMM_SKINNY_DMAW : GEMM_SKINNY_DMA;
     p.name = want_wide ? "gemm_nt_skinny_64cols_stream" : "gemm_nt_skinny_16cols_stream";
@@ -481,7 +485,7 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
     return p;
   }
-  if ((g.forced == GEMM_AUTO || g.forced == GEMM_SKINNY || g.forced == GEMM_SKINNY_DMA ||
+  if ((skinny_auto || g.forced == GEMM_SKINNY || g.forced == GEMM_SKINNY_DMA ||
        g.forced == GEMM_SKINNY_DMAW) && gemm_skinny_ok(g)) {
     p.variant = GEMM_SKINNY; p.name = "gemm_nt_skinny_16cols_ksplit8";
     p.bm = (int)((g.M + 15) / 16) * 16; p.bn = 16; p.bk = 32; p.wm = 1; p.wn = 1;

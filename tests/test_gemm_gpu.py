@@ -83,7 +83,7 @@ def test_skinny_kernel(shape, dtype):
     # M <= 64 with B stored N x K: one to four 16-row tiles, ragged N, K with and without a partial
     # last batch (K % 4096 != 0) and a partial last chunk (K % 32 != 0)
     M, N, K = shape
-    name, _ = _go(M, N, K, dtype, True, std=0.02, seed=7)
+    name, _ = _go(M, N, K, dtype, True, std=0.02, seed=7, variant="skinny")
     assert "skinny" in name
     # the same problem through the tile kernel must agree with the oracle too (and is what a
     # row-major B or a larger M gets)
@@ -106,14 +106,21 @@ def test_skinny_streaming_kernel(shape, dtype, form):
     assert name.endswith("cols_stream")
 
 
-def test_skinny_streaming_kernel_is_the_default_for_large_b():
-    # M <= 16 and B of 2^25 elements: routed to the streaming kernel without any override
+def test_skinny_routing():
+    # one 16-row tile of A and B of 2^25 elements: the streaming kernel without any override
     name, _ = _go(16, 8192, 4096, BF16, True, std=0.02, seed=9)
-    assert name.endswith("_stream")
-    name, _ = _go(17, 8192, 4096, BF16, True, std=0.02, seed=9)       # taller A, too few 64-column blocks
-    assert "skinny" in name and not name.endswith("_stream")
-    name, _ = _go(40, 16384, 2048, FP16, True, std=0.02, seed=9)      # taller A: the 64-column form
-    assert name == "gemm_nt_skinny_64cols_stream"
+    assert name.endswith("16cols_stream")
+    name, _ = _go(16, 4096, 4096, BF16, True, std=0.02, seed=9)       # smaller B: K split over the wavefronts
+    assert name.endswith("skinny_16cols_ksplit8")
+    name, _ = _go(30, 4096, 2048, BF16, True, std=0.02, seed=9)       # two row tiles, small B
+    assert name.endswith("skinny_16cols_ksplit8")
+    # taller A or two row tiles against a big B: the tile kernels (small tiles, K split inside the workgroup)
+    name, _ = _go(17, 8192, 4096, BF16, True, std=0.02, seed=9)
+    assert "skinny" not in name and "_k" in name
+    name, _ = _go(40, 16384, 2048, FP16, True, std=0.02, seed=9)
+    assert "skinny" not in name and "_k" in name
+    name, _ = _go(64, 4096, 4096, BF16, True, std=0.02, seed=9)
+    assert name.endswith("64x64x64_w2x2_k4")
 
 
 @pytest.mark.parametrize("variant", ["128k2", "64x128k2", "64k4"])
@@ -227,7 +234,8 @@ def test_config3_llm_shapes_transB(shape):
 
 
 @pytest.mark.parametrize("shape,suffix", [((16, 28672, 8192), "16cols_stream"), ((1, 28672, 8192), "16cols_stream"),
-                                          ((64, 28672, 4096), "64cols_stream"), ((16, 131072, 4096), "16cols_stream")])
+                                          ((64, 28672, 4096), "64x128x64_w2x4_k2"), ((16, 131072, 4096), "16cols_stream"),
+                                          ((32, 8192, 28672), "64x64x64_w2x2_k4")])
 def test_decode_shapes_streaming_kernels_full_size(shape, suffix):
     # the memory-bound decode GEMMs at their real sizes, in the launch configuration the library
     # picks (persistent workgroups, several column blocks each); sampled against the oracle
