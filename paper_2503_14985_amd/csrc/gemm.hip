@@ -466,17 +466,17 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.bm = 64; p.bn = 64; p.bk = 32; p.wm = 2; p.wn = 2;
     return p;
   }
-  // Skinny kernels (B stored N x K, no LDS staging of A): the automatic choice for one 16-row
-  // tile of A, streaming B through an LDS ring (16 columns x 512 k per stage) once B is well
-  // beyond the caches, and for two row tiles against a small B. Taller A goes to the tile kernels
-  // below: from two row tiles on they are faster (64 x 28672 x 8192: 102 us against 140 us for
-  // the 64-column streaming form, 64 x 14336 x 4096: 20 us against 79 us), because the skinny
-  // kernels re-read A from L2 for every 16 or 64 columns. The 64-column streaming form stays
-  // selectable (MLT_GEMM_VARIANT=skinnydmaw).
+  // Skinny kernels (B stored N x K, no LDS staging of A): the automatic choice for one or two
+  // 16-row tiles of A; B streamed through an LDS ring (16 columns x 512 k per stage, the A
+  // fragments of a k stage shared by a group of column blocks) once B is well beyond the caches.
+  // Taller A goes to the tile kernels below, which stage A through LDS once per tile: from three
+  // row tiles on they are faster (64 x 28672 x 8192: 92-103 us against 108 us for the 64-column
+  // streaming form and 177 us for the 16-column one; 64 x 14336 x 4096: 20 us against 28 / 43 us).
+  // The 64-column streaming form stays selectable (MLT_GEMM_VARIANT=skinnydmaw).
   const bool big_b = g.N * g.K >= ((int64_t)1 << 25);
-  const bool skinny_auto = g.forced == GEMM_AUTO && (g.M <= 16 || (g.M <= 32 && !big_b));
+  const bool skinny_auto = g.forced == GEMM_AUTO && g.M <= 32;
   const bool want_wide = g.forced == GEMM_SKINNY_DMAW;
-  const bool want_narrow = g.forced == GEMM_SKINNY_DMA || (skinny_auto && big_b && g.M <= 16);
+  const bool want_narrow = g.forced == GEMM_SKINNY_DMA || (skinny_auto && big_b);
   if ((want_wide || want_narrow) && gemm_skinny_dma_ok(g)) {
     p.variant = want_wide ? GEMM_SKINNY_DMAW : GEMM_SKINNY_DMA;
     p.name = want_wide ? "gemm_nt_skinny_64cols_stream" : "gemm_nt_skinny_16cols_stream";

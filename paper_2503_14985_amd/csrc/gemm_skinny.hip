@@ -202,9 +202,14 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int NS = (K + KS - 1) / KS;                        // stages per column block
   const int nblocks = (N + L::RPS - 1) / L::RPS;
-  // Persistent workgroups: this one owns column blocks blockIdx.x, + gridDim.x, ...; their stages
-  // form one stream g = 0 .. G-1 (block g / NS, k stage g % NS), so the ring never drains between
-  // blocks.
+  // Persistent workgroups: this one owns column blocks blockIdx.x, + gridDim.x, ... and takes
+  // them in groups of up to GB. The stages of a group are ordered k stage first: (k stage 0 of
+  // every block of the group), (k stage 1 of every block), ...; the accumulators of all the
+  // group's blocks stay in registers, and the A fragments of a k stage are fetched once per group
+  // instead of once per block. All stages of all groups form one stream g = 0 .. G-1, so the ring
+  // never drains between blocks or groups.
+  // (as many as the registers take: 8 blocks for one 16-row tile of A in the narrow form)
+  constexpr int GB = WIDE ? 2 : (MT == 1 ? 8 : MT == 2 ? 4 : 2);
   const int nmine = (nblocks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
   const int G = nmine * NS;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
@@ -212,13 +217,14 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
   if (wave < 4) {
     // ---- fetching wavefronts: load instruction ii of a stage fills LDS bytes ii*1024 .. +1023 of
     // the slot, i.e. rows ii*(64/LPR) .. of the stage; lane l serves row l / LPR of those at
-    // position l % LPR
-    auto issue_stage = [&](int g) {
-      const int bi = g / NS, ks = g - bi * NS;
-      const int n0 = ((int)blockIdx.x + bi * (int)gridDim.x) * L::RPS;
-      const int k0 = ks * KS;
+    // position l % LPR. The cursor (i_*) names the next stage of the stream to fetch.
+    int i_g = 0, i_base = 0, i_nb = nmine < GB ? nmine : GB, i_ks = 0, i_b = 0;
+    auto issue_next = [&]() __attribute__((always_inline)) {
+      if (i_g >= G) return;
+      const int n0 = ((int)blockIdx.x + (i_base + i_b) * (int)gridDim.x) * L::RPS;
+      const int k0 = i_ks * KS;
       const char* Bw = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
-      const uint32_t slot = lds0 + (uint32_t)(g % SD_ST) * SD_STAGE_B;
+      const uint32_t slot = lds0 + (uint32_t)(i_g % SD_ST) * SD_STAGE_B;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int ii = wave * 4 + i;
@@ -229,30 +235,39 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
         sd_load_lds16(Bw, (uint32_t)nrow * (uint32_t)ldb * 2u + (uint32_t)(k0 + ck * 8) * 2u,
                       slot + (uint32_t)ii * 1024u);
       }
+      ++i_g;
+      if (++i_b == i_nb) {
+        i_b = 0;
+        if (++i_ks == NS) {
+          i_ks = 0;
+          i_base += GB;
+          i_nb = nmine - i_base < GB ? nmine - i_base : GB;
+        }
+      }
     };
 #pragma unroll
-    for (int g = 0; g < SD_ST - 1; ++g)
-      if (g < G) issue_stage(g);
-    int ks = 0;
-    for (int g = 0; g < G; ++g) {
-      // issued so far: stages 0 .. min(G, g + SD_ST - 1) - 1; those after g may stay in flight
-      const int last = g + SD_ST - 2 < G - 1 ? g + SD_ST - 2 : G - 1;
-      switch (last - g) {
-        case 0: __builtin_amdgcn_s_waitcnt(sd_wait_imm(0)); break;
-        case 1: __builtin_amdgcn_s_waitcnt(sd_wait_imm(4)); break;
-        case 2: __builtin_amdgcn_s_waitcnt(sd_wait_imm(8)); break;
-        case 3: __builtin_amdgcn_s_waitcnt(sd_wait_imm(12)); break;
-        case 4: __builtin_amdgcn_s_waitcnt(sd_wait_imm(16)); break;
-        case 5: __builtin_amdgcn_s_waitcnt(sd_wait_imm(20)); break;
-        default: __builtin_amdgcn_s_waitcnt(sd_wait_imm(24)); break;
+    for (int t = 0; t < SD_ST - 1; ++t) issue_next();
+    int g = 0;
+    for (int base = 0; base < nmine; base += GB) {
+      const int nb = nmine - base < GB ? nmine - base : GB;
+      for (int t = 0; t < NS * nb; ++t, ++g) {
+        // issued so far: stages 0 .. min(G, g + SD_ST - 1) - 1; those after g may stay in flight
+        const int last = g + SD_ST - 2 < G - 1 ? g + SD_ST - 2 : G - 1;
+        switch (last - g) {
+          case 0: __builtin_amdgcn_s_waitcnt(sd_wait_imm(0)); break;
+          case 1: __builtin_amdgcn_s_waitcnt(sd_wait_imm(4)); break;
+          case 2: __builtin_amdgcn_s_waitcnt(sd_wait_imm(8)); break;
+          case 3: __builtin_amdgcn_s_waitcnt(sd_wait_imm(12)); break;
+          case 4: __builtin_amdgcn_s_waitcnt(sd_wait_imm(16)); break;
+          case 5: __builtin_amdgcn_s_waitcnt(sd_wait_imm(20)); break;
+          default: __builtin_amdgcn_s_waitcnt(sd_wait_imm(24)); break;
+        }
+        __builtin_amdgcn_s_barrier();                      // stage g is complete in LDS for everyone
+        issue_next();                                      // stage g + SD_ST - 1, into the slot of stage g-1 (read before this barrier)
       }
-      __builtin_amdgcn_s_barrier();                        // stage g is complete in LDS for everyone
-      if (g + SD_ST - 1 < G) issue_stage(g + SD_ST - 1);   // into the slot of stage g-1, read before this barrier
-      if (++ks == NS) {                                    // end of a column block: the reduction's barriers
-        ks = 0;
-#pragma unroll
-        for (int b = 0; b < 2 * MT - 1; ++b) __syncthreads();
-      }
+      // end of a group: the barriers of the computing wavefronts' reductions (two per block and
+      // row tile, less the very first)
+      for (int t = 0; t < 2 * nb * MT - 1; ++t) __syncthreads();
     }
   } else {
     // ---- computing wavefronts: wavefront cw takes k chunks J*cw .. J*cw + J-1 of every stage
@@ -266,11 +281,13 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
       ap[mt] = A + (int64_t)arow * lda;
     }
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    f32x4 acc[MT][NT];
+    f32x4 acc[GB][MT][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int gb = 0; gb < GB; ++gb)
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[gb][mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     // A fragments of k stage ks: k = ks*KS + (J*cw + j)*32 + 8*q
     auto load_a = [&](int ks, u32x4 (&af)[J][MT]) __attribute__((always_inline)) {
 #pragma unroll
@@ -281,68 +298,87 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
           af[j][mt] = *reinterpret_cast<const u32x4_mem*>(ap[mt] + (k < K ? k : 0));
       }
     };
-    int ks = 0, bi = 0;
-    // one stage: `cur` holds its A fragments, those of the next stage are requested into `nxt`
-    auto step = [&](int g, u32x4 (&cur)[J][MT], u32x4 (&nxt)[J][MT]) __attribute__((always_inline)) {
-      __builtin_amdgcn_s_barrier();
-      const uint32_t slot = lds0 + (uint32_t)(g % SD_ST) * SD_STAGE_B;
-      u32x4 bf[J][NT];
-#pragma unroll
-      for (int j = 0; j < J; ++j) {
-        const int c16 = (J * cw + j) * 4 + q;                // 16-byte chunk of the row piece
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-          bf[j][nt] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(
-              slot + (uint32_t)(nt * 16 + r16) * L::PB + (uint32_t)((c16 ^ r16) << 4));
-      }
-      load_a(ks + 1 < NS ? ks + 1 : 0, nxt);               // unconditional: keeps the load counting exact
-      const bool whole = (ks + 1) * KS <= K;
-#pragma unroll
-      for (int j = 0; j < J; ++j) {
-        const bool dead = !whole && ks * KS + (J * cw + j) * 32 + 8 * q >= K;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const u32x4 a = dead ? zero4 : cur[j][mt];
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt) {
-            const u32x4 b = dead ? zero4 : bf[j][nt];
-            acc[mt][nt] = mfma16(__builtin_bit_cast(V8, a), __builtin_bit_cast(V8, b), acc[mt][nt]);
-          }
-        }
-      }
-      if (++ks == NS) {
-        // end of a column block: per 16-row tile of A the four wavefronts' partial tiles meet in
-        // LDS, 256 lanes add them and store (2*MT - 1 barriers, matched by the fetching wavefronts)
-        ks = 0;
-        const int n0 = ((int)blockIdx.x + bi * (int)gridDim.x) * L::RPS;
-        ++bi;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          if (mt > 0) __syncthreads();                       // the previous tile's sums have been read
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              red[(cw * NT + nt) * 256 + (4 * q + r) * 16 + r16] = acc[mt][nt][r];
-              acc[mt][nt][r] = 0.f;
-            }
-          __syncthreads();                                   // with the fence: the partial tiles are LDS stores
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt) {
-            float sum = 0.f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) sum += red[(w * NT + nt) * 256 + ctid];
-            const int gr = mt * 16 + (ctid >> 4), gc = n0 + nt * 16 + (ctid & 15);
-            if (gr < M && gc < N) C[(int64_t)gr * ldc + gc] = Elem<Tag>::from_f32(sum);
-          }
-        }
-      }
-    };
+    int g = 0;
     u32x4 af0[J][MT], af1[J][MT];
     load_a(0, af0);
-    for (int g = 0; g < G; g += 2) {
-      step(g, af0, af1);
-      if (g + 1 < G) step(g + 1, af1, af0);
+    for (int base = 0; base < nmine; base += GB) {
+      const int nb = nmine - base < GB ? nmine - base : GB;
+      // k stage ks of every block of the group: `cur` holds its A fragments; those of the next k
+      // stage (of this group, or stage 0 for the next group) are requested into `nxt` meanwhile
+      auto k_stage = [&](int ks, u32x4 (&cur)[J][MT], u32x4 (&nxt)[J][MT]) __attribute__((always_inline)) {
+        const bool whole = (ks + 1) * KS <= K;
+#pragma unroll
+        for (int gb = 0; gb < GB; ++gb) {
+          if (gb < nb) {
+            __builtin_amdgcn_s_barrier();
+            const uint32_t slot = lds0 + (uint32_t)(g % SD_ST) * SD_STAGE_B;
+            u32x4 bf[J][NT];
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+              const int c16 = (J * cw + j) * 4 + q;              // 16-byte chunk of the row piece
+#pragma unroll
+              for (int nt = 0; nt < NT; ++nt)
+                bf[j][nt] = *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(
+                    slot + (uint32_t)(nt * 16 + r16) * L::PB + (uint32_t)((c16 ^ r16) << 4));
+            }
+            if (gb == 0) load_a(ks + 1 < NS ? ks + 1 : 0, nxt);  // unconditional: keeps the load counting exact
+#pragma unroll
+            for (int j = 0; j < J; ++j) {
+              const bool dead = !whole && ks * KS + (J * cw + j) * 32 + 8 * q >= K;
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) {
+                const u32x4 a = dead ? zero4 : cur[j][mt];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                  const u32x4 bb = dead ? zero4 : bf[j][nt];
+                  acc[gb][mt][nt] = mfma16(__builtin_bit_cast(V8, a), __builtin_bit_cast(V8, bb), acc[gb][mt][nt]);
+                }
+              }
+            }
+            ++g;
+          }
+        }
+      };
+      for (int ks = 0; ks < NS; ks += 2) {
+        k_stage(ks, af0, af1);
+        if (ks + 1 < NS) k_stage(ks + 1, af1, af0);
+      }
+      if (NS & 1) {
+        // an odd number of k stages leaves the fragments of the next group's stage 0 in af1
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) af0[j][mt] = af1[j][mt];
+      }
+      // end of a group: per block and 16-row tile of A the four wavefronts' partial tiles meet in
+      // LDS, 256 lanes add them and store (2 * nb * MT - 1 barriers, matched by the fetching
+      // wavefronts)
+#pragma unroll
+      for (int gb = 0; gb < GB; ++gb) {
+        if (gb < nb) {
+          const int n0 = ((int)blockIdx.x + (base + gb) * (int)gridDim.x) * L::RPS;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            if (gb > 0 || mt > 0) __syncthreads();             // the previous sums have been read
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                red[(cw * NT + nt) * 256 + (4 * q + r) * 16 + r16] = acc[gb][mt][nt][r];
+                acc[gb][mt][nt][r] = 0.f;
+              }
+            __syncthreads();                                   // with the fence: the partial tiles are LDS stores
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+              float sum = 0.f;
+#pragma unroll
+              for (int w = 0; w < 4; ++w) sum += red[(w * NT + nt) * 256 + ctid];
+              const int gr = mt * 16 + (ctid >> 4), gc = n0 + nt * 16 + (ctid & 15);
+              if (gr < M && gc < N) C[(int64_t)gr * ldc + gc] = Elem<Tag>::from_f32(sum);
+            }
+          }
+        }
+      }
     }
   }
 }

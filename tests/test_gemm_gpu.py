@@ -94,29 +94,31 @@ def test_skinny_kernel(shape, dtype):
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("shape", [(16, 1024, 512), (1, 1031, 520), (17, 2048, 4096 + 8), (64, 1040, 1024),
                                    (33, 4096, 8), (48, 1500, 7000), (16, 16 * 300 + 5, 1536),
-                                   (20, 64 * 300 + 21, 1160)])
+                                   (20, 64 * 300 + 21, 1160), (16, 40965, 520), (8, 36880, 1536)])
 @pytest.mark.parametrize("form", ["skinnydma", "skinnydmaw"])
 def test_skinny_streaming_kernel(shape, dtype, form):
     # B streamed through the LDS ring by persistent workgroups, in both stage shapes (16 columns x
     # 512 k, 64 columns x 128 k): one to four 16-row tiles of A, ragged N (clamped rows), K below /
     # equal to / not a multiple of the stage, a single 8-wide K, and more column blocks than CUs
-    # (several blocks per workgroup, the ring wrapping across block ends)
+    # (several blocks per workgroup, the ring wrapping across block ends; the last two shapes give
+    # a workgroup more blocks than one group holds: full and partial groups, odd and even numbers
+    # of k stages)
     M, N, K = shape
     name, _ = _go(M, N, K, dtype, True, std=0.02, seed=8, variant=form)
     assert name.endswith("cols_stream")
 
 
 def test_skinny_routing():
-    # one 16-row tile of A and B of 2^25 elements: the streaming kernel without any override
+    # one or two 16-row tiles of A and B of 2^25 elements: the streaming kernel without any override
     name, _ = _go(16, 8192, 4096, BF16, True, std=0.02, seed=9)
+    assert name.endswith("16cols_stream")
+    name, _ = _go(17, 8192, 4096, BF16, True, std=0.02, seed=9)
     assert name.endswith("16cols_stream")
     name, _ = _go(16, 4096, 4096, BF16, True, std=0.02, seed=9)       # smaller B: K split over the wavefronts
     assert name.endswith("skinny_16cols_ksplit8")
-    name, _ = _go(30, 4096, 2048, BF16, True, std=0.02, seed=9)       # two row tiles, small B
+    name, _ = _go(30, 4096, 2048, BF16, True, std=0.02, seed=9)
     assert name.endswith("skinny_16cols_ksplit8")
-    # taller A or two row tiles against a big B: the tile kernels (small tiles, K split inside the workgroup)
-    name, _ = _go(17, 8192, 4096, BF16, True, std=0.02, seed=9)
-    assert "skinny" not in name and "_k" in name
+    # taller A: the tile kernels (small tiles, K split inside the workgroup)
     name, _ = _go(40, 16384, 2048, FP16, True, std=0.02, seed=9)
     assert "skinny" not in name and "_k" in name
     name, _ = _go(64, 4096, 4096, BF16, True, std=0.02, seed=9)
@@ -235,7 +237,7 @@ def test_config3_llm_shapes_transB(shape):
 
 @pytest.mark.parametrize("shape,suffix", [((16, 28672, 8192), "16cols_stream"), ((1, 28672, 8192), "16cols_stream"),
                                           ((64, 28672, 4096), "64x128x64_w2x4_k2"), ((16, 131072, 4096), "16cols_stream"),
-                                          ((32, 8192, 28672), "64x64x64_w2x2_k4")])
+                                          ((32, 8192, 28672), "16cols_stream"), ((64, 8192, 28672), "64x64x64_w2x2_k4")])
 def test_decode_shapes_streaming_kernels_full_size(shape, suffix):
     # the memory-bound decode GEMMs at their real sizes, in the launch configuration the library
     # picks (persistent workgroups, several column blocks each); sampled against the oracle
