@@ -75,8 +75,8 @@ int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
  *          2  vertical: evenly along the columns only, 8 wavefronts x (256 x 32)
  *          3  square: 2 x 2 wavefronts x (128 x 128)
  * The hint applies to operands that allow 16-byte vector access (see mlt_gemm); others take the
- * general kernel, K = 0 stores zeros, and M <= 64 with B stored N x K keeps the skinny kernels
- * only for tiling 0. Returns as mlt_gemm; MLT_ERR_INVALID_ARG also for an unknown `tiling`.
+ * general kernel, K = 0 stores zeros, and the skinny kernels (M <= 32 with B stored N x K) and
+ * the smaller workgroup tiles of small problems are chosen only for tiling 0. Returns as mlt_gemm; MLT_ERR_INVALID_ARG also for an unknown `tiling`.
  */
 int mlt_gemm_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
                    int64_t ldb, int transB, void* C, int64_t ldc, int dtype, int tiling,

@@ -2,10 +2,11 @@
 //
 // Same three levels as the paper's GEMM (arXiv 2503.14985, Sections 2.1-2.3: workgroup tile,
 // per-warp sub-tile, hardware dot): workgroup tile 256 x 256, K step 64, 8 wavefronts as 2 x 4
-// owning 128 x 64 each, MFMA 32x32x16. What differs from gemm.hip is how memory traffic and
+// owning 128 x 64 each, MFMA 16x16x32 (MS = 16, the form the library uses) or 32x32x16 (MS = 32).
+// What differs from gemm.hip is how memory traffic and
 // matrix work overlap. A CU runs one workgroup, two wavefronts per SIMD. The two wavefronts of a
 // SIMD are kept half a K step apart by one extra barrier at the start: while one of them issues
-// its 32 MFMAs of a K step back to back (compute phase), the other refills its operand fragments
+// its 64 (or 32) MFMAs of a K step back to back (compute phase), the other refills its operand fragments
 // from LDS for its next compute phase (memory phase). Every phase ends in a workgroup barrier, so
 // the matrix pipe of each SIMD always has exactly one wavefront feeding it and LDS latency never
 // sits in front of an MFMA.

@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Times the library over sets of shapes and prints markdown tables (one MI355X, synthetic data).
 
-  python3 paper_2503_14985_amd/sweep.py gemm [--torch]   GEMM shapes: the square sweep, the LLM
+  python3 paper_2503_14985_amd/sweep.py gemm [--torch] [--dtype fp16]
+                                                          GEMM shapes: the square sweep, the LLM
                                                           shapes with B stored N x K, mid-size and
                                                           decode (skinny) shapes
   python3 paper_2503_14985_amd/sweep.py fa2              attention forward over the sweep of the
@@ -51,15 +52,15 @@ def _timeit(torch, fn, n):
     return e0.elapsed_time(e1) / n
 
 
-def sweep_gemm(torch, binding, dev, with_torch):
+def sweep_gemm(torch, binding, dev, with_torch, dt):
     head = "| M x N x K | B stored | kernel | us | TFLOP/s | GB/s (A+B+C once) |"
     print(head + (" torch us |" if with_torch else ""))
     print("|---|---|---|---|---|---|" + ("---|" if with_torch else ""))
     for (M, N, K, tb) in GEMM_SHAPES:
         std = 0.02 if tb else 1.0
-        A = torch.randn(M, K, device=dev, dtype=torch.bfloat16) * std
-        B = torch.randn((N, K) if tb else (K, N), device=dev, dtype=torch.bfloat16) * std
-        C = torch.empty(M, N, device=dev, dtype=torch.bfloat16)
+        A = (torch.randn(M, K, device=dev, dtype=torch.float32) * std).to(dt)
+        B = (torch.randn((N, K) if tb else (K, N), device=dev, dtype=torch.float32) * std).to(dt)
+        C = torch.empty(M, N, device=dev, dtype=dt)
         n = 20 if M * N * K > 1e11 else 100
         ms = min(_timeit(torch, lambda: binding.mlt_gemm(A, B, C=C, transB=tb), n) for _ in range(2))
         line = "| %d x %d x %d | %s | `%s` | %.1f | %.0f | %.0f |" % (
@@ -97,6 +98,7 @@ def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("what", choices=["gemm", "fa2"])
     ap.add_argument("--torch", action="store_true", help="gemm: add torch.matmul on the same tensors")
+    ap.add_argument("--dtype", choices=["bf16", "fp16"], default="bf16", help="gemm: element type")
     args = ap.parse_args()
     import torch
     from paper_2503_14985_amd import binding   # raises if libmlt.so is missing
@@ -104,7 +106,7 @@ def main():
     torch.cuda.set_device(dev)
     torch.manual_seed(0)
     if args.what == "gemm":
-        sweep_gemm(torch, binding, dev, args.torch)
+        sweep_gemm(torch, binding, dev, args.torch, torch.bfloat16 if args.dtype == "bf16" else torch.float16)
     else:
         sweep_fa2(torch, binding, dev)
 
