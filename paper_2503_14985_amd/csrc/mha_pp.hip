@@ -70,6 +70,23 @@ __device__ __forceinline__ float both_halves_sum(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
 }
+// O^T accumulators -> 16-byte pieces of O rows. A lane holds, of its query row, 4 consecutive d
+// per register group g (d = 32t + 8g + 4h + 0..3, h = lane / 32): 8-byte pieces, which the lane
+// with the other h interleaves. Swapping group g+1 of the lower lanes with group g of the upper
+// ones (permlane32_swap, per packed register) leaves the lower lane with d = 32t + 8g + 0..7 and
+// the upper lane with the next 8: one 16-byte store each instead of two 8-byte ones, and 32
+// contiguous bytes per row and store instruction.
+template <typename Tag>
+__device__ __forceinline__ u32x4 o_piece16(const f32x16& acc, int g, float inv) {
+  const uint32_t a0 = Elem<Tag>::pack2(acc[4 * g] * inv, acc[4 * g + 1] * inv);
+  const uint32_t a1 = Elem<Tag>::pack2(acc[4 * g + 2] * inv, acc[4 * g + 3] * inv);
+  const uint32_t b0 = Elem<Tag>::pack2(acc[4 * g + 4] * inv, acc[4 * g + 5] * inv);
+  const uint32_t b1 = Elem<Tag>::pack2(acc[4 * g + 6] * inv, acc[4 * g + 7] * inv);
+  auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+  auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+  return u32x4{(uint32_t)s0[0], (uint32_t)s1[0], (uint32_t)s0[1], (uint32_t)s1[1]};
+}
+
 __device__ __forceinline__ float max3(float a, float b, float c) {
   return __builtin_fmaxf(__builtin_fmaxf(a, b), c);       // v_max3_f32
 }
@@ -443,20 +460,20 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
 #undef MLT_SB
   if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
 
-  // ---- epilogue: O = O^T / l, l summed over both key halves; 4 consecutive d per store
+  // ---- epilogue: O = O^T / l, l summed over both key halves; 8 consecutive d per store
   const float l_tot = both_halves_sum(l_run);
   const float inv = 1.f / l_tot;
+  u32x4 ow[NDT][2];
+#pragma unroll
+  for (int t = 0; t < NDT; ++t)
+#pragma unroll
+    for (int gp = 0; gp < 2; ++gp) ow[t][gp] = o_piece16<Tag>(o_acc[t], 2 * gp, inv);
   if (my_q < Sq) {
-    uint16_t* op = O + ((int64_t)bh * Sq + my_q) * D + 4 * h;
+    uint16_t* op = O + ((int64_t)bh * Sq + my_q) * D + 8 * h;
 #pragma unroll
     for (int t = 0; t < NDT; ++t)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 w;
-        w[0] = Elem<Tag>::pack2(o_acc[t][4 * g] * inv, o_acc[t][4 * g + 1] * inv);
-        w[1] = Elem<Tag>::pack2(o_acc[t][4 * g + 2] * inv, o_acc[t][4 * g + 3] * inv);
-        *reinterpret_cast<u32x2_mem*>(op + t * 32 + 8 * g) = w;
-      }
+      for (int gp = 0; gp < 2; ++gp) *reinterpret_cast<u32x4_mem*>(op + t * 32 + 16 * gp) = ow[t][gp];
   }
 }
 
@@ -492,7 +509,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_ps_kernel(
   constexpr int NKK = L::NKK, NDT = L::NDT, ROWB = L::ROWB;
   constexpr int LPT = 2 * L::LPW;    // K/V loads per wavefront per tile
   constexpr int NQL = NKK;           // loads per wavefront that fetch a Q operand
-  constexpr int NST = 4 * NDT;       // stores per wavefront that write an O tile
+  constexpr int NST = 2 * NDT;       // stores per wavefront that write an O tile
   extern __shared__ __align__(16) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -685,17 +702,17 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_ps_kernel(
     const int my_q_ = q0_ + lq;
     const float l_tot = both_halves_sum(l_run);
     const float inv = 1.f / l_tot;
+    u32x4 ow[NDT][2];
+#pragma unroll
+    for (int t = 0; t < NDT; ++t)
+#pragma unroll
+      for (int gp = 0; gp < 2; ++gp) ow[t][gp] = o_piece16<Tag>(o_acc[t], 2 * gp, inv);
     if (my_q_ < Sq) {
-      uint16_t* op = O + ((int64_t)bh_ * Sq + my_q_) * D + 4 * h;
+      uint16_t* op = O + ((int64_t)bh_ * Sq + my_q_) * D + 8 * h;
 #pragma unroll
       for (int t = 0; t < NDT; ++t)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          u32x2 w;
-          w[0] = Elem<Tag>::pack2(o_acc[t][4 * g] * inv, o_acc[t][4 * g + 1] * inv);
-          w[1] = Elem<Tag>::pack2(o_acc[t][4 * g + 2] * inv, o_acc[t][4 * g + 3] * inv);
-          *reinterpret_cast<u32x2_mem*>(op + t * 32 + 8 * g) = w;
-        }
+        for (int gp = 0; gp < 2; ++gp) *reinterpret_cast<u32x4_mem*>(op + t * 32 + 16 * gp) = ow[t][gp];
     }
 #pragma unroll
     for (int t = 0; t < NDT; ++t)
