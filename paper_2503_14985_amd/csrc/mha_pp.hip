@@ -813,10 +813,14 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_ps_kernel(
     if (grp == 0) {
       // needed: tile g+1. Issued after it: tiles g+2, g+3 (those that exist), the O stores of this
       // or the last two tiles' softmax phases, this phase's Q loads.
-      int n = ((g + 3 < NT ? 1 : 0) + (g + 2 < NT ? 1 : 0)) * LPT;
-      if (st_age <= 2) n += NST;
-      if (last) n += NQL;
-      wait_vm0(n);
+      if (g + 3 < NT && st_age > 2 && !last) {             // the steady state: one test, one wait
+        __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 0));
+      } else {
+        int n = ((g + 3 < NT ? 1 : 0) + (g + 2 < NT ? 1 : 0)) * LPT;
+        if (st_age <= 2) n += NST;
+        if (last) n += NQL;
+        wait_vm0(n);
+      }
     } else {
       __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
     }
@@ -869,9 +873,13 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_ps_kernel(
     if (grp == 1) {
       // needed: tile g+2. Issued after it: tile g+3 (if it exists) and the O stores of this tile's
       // or the previous tile's softmax phase.
-      int n = g + 3 < NT ? LPT : 0;
-      if (st_age <= 1) n += NST;
-      wait_vm15(n);
+      if (g + 3 < NT && st_age > 1) {
+        __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
+      } else {
+        int n = g + 3 < NT ? LPT : 0;
+        if (st_age <= 1) n += NST;
+        wait_vm15(n);
+      }
     }
     __builtin_amdgcn_s_barrier();
     MLT_SB();

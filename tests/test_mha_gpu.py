@@ -80,7 +80,7 @@ def test_persistent_kernel_walks_items(grid, D, dtype):
     assert binding.mlt_last_kernel().endswith("_pp")
     _go(1, 2, 300, 200, D, dtype, True, seed=6)
     assert binding.mlt_last_kernel().endswith("_pp")
-    # default routing: D = 128 with at most 16 key tiles per item
+    # default routing: D = 128 with at most 8 key tiles per item
     os.environ.pop("MLT_MHA_VARIANT", None)
     _go(1, 2, 300, 200, D, dtype, False, seed=7)
     assert binding.mlt_last_kernel().endswith("_ps" if D == 128 else "_pp")
