@@ -128,3 +128,23 @@ def test_tiling_query_is_the_papers_partition_rule(binding):
     assert a[2:4] == [8, 1] and a[4] == a[0] // 8 and a[5] == 128 and a[9] == 64
     with pytest.raises(binding.MltError):
         binding.mlt_query_tiling(1, (4096, 4096, 80, 0), 0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Everything here runs on one GPU; bench.py says so instead of pretending to scale."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
+
+
+def test_sweep_tool_parses_its_arguments():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "paper_2503_14985_amd", "sweep.py"), "--help"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "fa2" in r.stdout
