@@ -310,6 +310,37 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   // 4*(l/16) + r; the column is the lane's
   const int row_base = m0 + wm * 128 + 4 * h;
   const int col_base = n0 + wn * 64 + lq;
+  if constexpr (MS == 16) {
+    // Plain 16-bit store with even N and ldc: neighbouring lanes (columns c, c+1 of the same four
+    // rows) exchange two of their four values, so that the even lane holds rows 0, 1 and the odd
+    // lane rows 2, 3 of BOTH columns: two 32-bit stores per tile and lane instead of four 16-bit
+    // ones (the stores are what the epilogue spends its time on).
+    const bool pairs = epi == 0 && bias == nullptr && !(N & 1) && !(ldc & 1) &&
+                       !(reinterpret_cast<uintptr_t>(C) & 3);
+    if (pairs) {
+      const bool odd = lane & 1;
+      auto neighbour = [](float x) {                      // the value lane l ^ 1 passes in
+        return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+      };
+      const int col0 = col_base - (odd ? 1 : 0);
+#pragma unroll
+      for (int i = 0; i < TA; ++i)
+#pragma unroll
+        for (int j = 0; j < TB; ++j) {
+          const float got0 = neighbour(odd ? acc[i][j][0] : acc[i][j][2]);
+          const float got1 = neighbour(odd ? acc[i][j][1] : acc[i][j][3]);
+          const uint32_t w0 = odd ? Elem<Tag>::pack2(got0, acc[i][j][2]) : Elem<Tag>::pack2(acc[i][j][0], got0);
+          const uint32_t w1 = odd ? Elem<Tag>::pack2(got1, acc[i][j][3]) : Elem<Tag>::pack2(acc[i][j][1], got1);
+          const int row = row_base + i * 16 + (odd ? 2 : 0);
+          const int col = col0 + j * 16;
+          if (col < N) {
+            if (row < M) *reinterpret_cast<uint32_t*>(C + (int64_t)row * ldc + col) = w0;
+            if (row + 1 < M) *reinterpret_cast<uint32_t*>(C + (int64_t)(row + 1) * ldc + col) = w1;
+          }
+        }
+      return;
+    }
+  }
   gemm_epilogue<Tag>([&](auto&& out) {
 #pragma unroll
     for (int i = 0; i < TA; ++i)

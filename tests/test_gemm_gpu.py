@@ -63,6 +63,16 @@ def test_two_group_kernel(shape, transB, dtype, form):
     assert name.endswith("_pp16" if form == "256pp16" else "_pp")
 
 
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+@pytest.mark.parametrize("case", [(300, 263, 128, 0), (259, 520, 192, 1), (259, 520, 192, 3), (513, 262, 64, 2)])
+def test_two_group_kernel_store_forms(case, dtype):
+    # the 16x16x32 form stores pairs of columns as 32-bit words when N and ldc are even and falls
+    # back to element stores otherwise: odd N (B stored N x K), odd and even padded ldc, odd M
+    M, N, K, ldc_pad = case
+    name, _ = _go(M, N, K, dtype, True, variant="256pp16", seed=13, ldc_pad=ldc_pad)
+    assert name.endswith("_pp16")
+
+
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("shape", [(520, 776, 320), (512, 768, 256), (100, 40, 64), (257, 264, 128),
