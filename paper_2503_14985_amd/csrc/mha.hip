@@ -384,12 +384,11 @@ MhaPlan plan_mha(const MhaArgs& a) {
     // The persistent form ("ps" forces it wherever it applies). Measured, unmasked, 2048 items,
     // time per item against the per-item kernel: D = 128 gains 25 % at 2 key tiles per item, 8 %
     // at 4, 3 % at 8 and loses 1.5 % at 16, 3 % at 32 and 4 % at 64 (its loop carries the item
-    // bookkeeping); D = 64, where two workgroups per CU already cover each other's start and end,
-    // loses 10 % everywhere.
-    const bool ps_pays = a.D == 128 && a.Sk <= 8 * 64;
+    // bookkeeping). D = 64 has no persistent form (mha_ps_ok).
+    const bool ps_pays = a.Sk <= 8 * 64;
     p.persistent = mha_ps_ok(a) && (e ? !strcmp(e, "ps") : ps_pays);
     if (p.persistent) {
-      p.name = a.D == 128 ? "mha_fwd_d128_256x64_ps" : "mha_fwd_d64_256x64_ps";
+      p.name = "mha_fwd_d128_256x64_ps";
       return p;
     }
     if (p.mfma_size == 16) {

@@ -483,7 +483,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
 // (batch*head, query tile) item and exits pays, per item, for its launch, the latency of the Q
 // load, the latency of the first K/V tiles, the one-phase stagger of the two groups at both ends
 // and the draining of the O stores: about 10 us per item for D = 128, against 1.7 us per key tile.
-// Here the grid is one workgroup per CU (two for D = 64) and each workgroup walks through items
+// Here the grid is one workgroup per CU and each workgroup walks through items
 // blockIdx.x, blockIdx.x + gridDim.x, ... as ONE stream of K/V tiles: the ring of LDS slots, the
 // prefetch distance and the phase structure run on across item boundaries, so the first tiles of
 // the next item are already in LDS when the current item ends. At a boundary
@@ -500,7 +500,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
 // waits below add the Q loads / O stores to N only where they are certain to have been issued (a
 // wavefront whose query rows all lie beyond Sq issues no stores and adds nothing).
 template <typename Tag, int D>
-__global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_ps_kernel(
+__global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int Sq, int Sk, int nq, int total,
     float c, int negate) {
@@ -1295,10 +1295,10 @@ int launch_mha_pp(const MhaArgs& a, hipStream_t s) {
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
-// The persistent kernel: one workgroup per CU (two for D = 64, which leaves room for them), at
-// most one per item.
+// The persistent kernel: one workgroup per CU, at most one per item.
 template <typename Tag, int D>
 int launch_mha_ps(const MhaArgs& a, hipStream_t s) {
+  static_assert(D == 128, "see mha_ps_ok");
   typedef PaCfg<D> L;
   auto kern = mha_ps_kernel<Tag, D>;
   static thread_local int configured_dev = -1;          // opt in to > 64 KB LDS once per device
@@ -1317,7 +1317,7 @@ int launch_mha_ps(const MhaArgs& a, hipStream_t s) {
   }
   const int nq = (int)((a.Sq + PA_BM - 1) / PA_BM);
   const int64_t total = a.B * a.H * nq;
-  int64_t slots = (int64_t)ncu * (D == 64 ? 2 : 1);
+  int64_t slots = ncu;
   // Tuning/test override: MLT_MHA_PS_GRID = number of workgroups (small values make every
   // workgroup walk through many items even on a small problem).
   if (const char* e = getenv("MLT_MHA_PS_GRID")) {
@@ -1347,7 +1347,12 @@ bool mha_pp_ok(const MhaArgs& a) { return (a.D == 64 || a.D == 128) && a.Sk * a.
 
 // The persistent kernel takes the unmasked case with at least two key tiles per item; the item
 // and stream-tile counters are 32-bit.
+// D = 128 only: at the 128 registers that D = 64 is compiled for (two workgroups per CU) the compiler
+// spills a Q register while its inline-assembly load is still in flight, which the schedule's
+// own wait cannot cover (and the persistent form measured 10 % slower than the per-item kernel
+// there anyway).
 bool mha_ps_ok(const MhaArgs& a) {
+  if (a.D != 128) return false;
   if (!mha_pp_ok(a) || a.causal || a.Sk <= PA_BN || a.Sq < 1 || a.B * a.H < 1) return false;
   const int64_t nq = (a.Sq + PA_BM - 1) / PA_BM, nblk = (a.Sk + PA_BN - 1) / PA_BN;
   const int64_t total = a.B * a.H * nq;
@@ -1356,8 +1361,7 @@ bool mha_ps_ok(const MhaArgs& a) {
 
 int run_mha_ps(const MhaArgs& a, hipStream_t s) {
   if (!mha_ps_ok(a)) return MLT_ERR_UNSUPPORTED;
-  if (a.D == 128) return a.dtype == MLT_BF16 ? launch_mha_ps<bf16_tag, 128>(a, s) : launch_mha_ps<f16_tag, 128>(a, s);
-  return a.dtype == MLT_BF16 ? launch_mha_ps<bf16_tag, 64>(a, s) : launch_mha_ps<f16_tag, 64>(a, s);
+  return a.dtype == MLT_BF16 ? launch_mha_ps<bf16_tag, 128>(a, s) : launch_mha_ps<f16_tag, 128>(a, s);
 }
 
 int run_mha_pp(const MhaArgs& a, int mfma_size, hipStream_t s) {

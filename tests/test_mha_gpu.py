@@ -60,8 +60,8 @@ def test_every_kernel_variant(variant, suffix, causal, D, dtype):
 
 
 @pytest.mark.parametrize("grid", [1, 3, 8, 0])
-@pytest.mark.parametrize("D,dtype", [(128, BF16), (64, FP16), (128, FP16), (64, BF16)])
-def test_persistent_kernel_walks_items(grid, D, dtype):
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+def test_persistent_kernel_walks_items(grid, dtype, D=128):
     """The unmasked case runs in the persistent kernel: every workgroup walks through several
     (head, query tile) items as one stream of key tiles. Few workgroups (the grid override) make
     each of them cross many item boundaries: 2 to 7 key tiles per item, ragged key and query ends
@@ -80,10 +80,13 @@ def test_persistent_kernel_walks_items(grid, D, dtype):
     assert binding.mlt_last_kernel().endswith("_pp")
     _go(1, 2, 300, 200, D, dtype, True, seed=6)
     assert binding.mlt_last_kernel().endswith("_pp")
+    # D = 64 has no persistent form, forced or not
+    _go(1, 2, 300, 200, 64, dtype, False, seed=9)
+    assert binding.mlt_last_kernel().endswith("_pp")
     # default routing: D = 128 with at most 8 key tiles per item
     os.environ.pop("MLT_MHA_VARIANT", None)
     _go(1, 2, 300, 200, D, dtype, False, seed=7)
-    assert binding.mlt_last_kernel().endswith("_ps" if D == 128 else "_pp")
+    assert binding.mlt_last_kernel().endswith("_ps")
     _go(1, 1, 256, 1100, D, dtype, False, seed=8)
     assert binding.mlt_last_kernel().endswith("_pp")
 
