@@ -60,3 +60,31 @@ def test_persistent_attention_q_registers_are_left_alone_while_loading(tmp_path)
             # and the wait that the schedule supplies sits in front of that first use
             back = [l for l in lines[group[-1]:j] if l.startswith("s_waitcnt") and "vmcnt" in l]
             assert back, "%s: no vmcnt wait between the Q loads and their first use" % name[-30:]
+
+
+def _compile_to_asm(src, tmp_path):
+    import __graft_entry__ as entry
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("no hipcc here")
+    out = tmp_path / (src + ".s")
+    flags = [f for f in entry.HIPCC_FLAGS if f != "-fPIC"]
+    subprocess.check_call([hipcc] + flags + ["-S", "--cuda-device-only", "-o", str(out),
+                                             os.path.join(entry.CSRC, src)], stderr=subprocess.DEVNULL)
+    return out.read_text()
+
+
+def test_headline_kernels_keep_their_registers(tmp_path):
+    """The two kernels of the benchmark step must not spill (no scratch memory) and must fit the
+    occupancy their launch assumes: 8 wavefronts per CU = 2 per SIMD = at most 256 registers."""
+    for src, pattern in (("gemm_pp.hip", r"gemm_pp_kernel\S*"), ("mha_pp.hip", r"mha_pp_kernelINS_\w+_tagELi128\S*")):
+        asm = _compile_to_asm(src, tmp_path)
+        found = 0
+        for m in re.finditer(r"^(_Z\S*" + pattern + r"):.*?\n(.*?)\.end_amdhsa_kernel", asm, re.S | re.M):
+            body, tail = m.group(2), asm[m.end():m.end() + 4000]
+            scratch = int(re.search(r"; ScratchSize: (\d+)", tail).group(1))
+            vgprs = int(re.search(r"\.amdhsa_next_free_vgpr (\d+)", body).group(1))
+            assert scratch == 0, "%s spills %d bytes" % (m.group(1)[-40:], scratch)
+            assert vgprs <= 256
+            found += 1
+        assert found >= 4, (src, found)
