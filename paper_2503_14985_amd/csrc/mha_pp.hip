@@ -460,7 +460,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
 #undef MLT_SB
   if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
 
-  // ---- epilogue: O = O^T / l, l summed over both key halves; 8 consecutive d per store
+  // ---- epilogue: O = O^T / l, l summed over both key halves; 8 consecutive d per lane and piece
   const float l_tot = both_halves_sum(l_run);
   const float inv = 1.f / l_tot;
   u32x4 ow[NDT][2];
@@ -468,12 +468,26 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
   for (int t = 0; t < NDT; ++t)
 #pragma unroll
     for (int gp = 0; gp < 2; ++gp) ow[t][gp] = o_piece16<Tag>(o_acc[t], 2 * gp, inv);
-  if (my_q < Sq) {
-    uint16_t* op = O + ((int64_t)bh * Sq + my_q) * D + 8 * h;
+  // Through LDS (the ring is free: every wavefront is past its last tile read after the barrier
+  // above), so that a store instruction writes whole rows: the wavefront parks its 32 rows in its
+  // own 32 * ROWB bytes, 16-byte chunk ch of row r at position ch ^ (r % chunks per row), and
+  // reads them back 64 / chunks-per-row rows at a time, 1 KB contiguous in O per store. Only the
+  // wavefront's own data is involved, and LDS serves a wavefront's accesses in order: no barrier.
+  const uint32_t o_lds = lds0 + wave * 32 * ROWB;
+  constexpr int CM = L::CPR - 1;
 #pragma unroll
-    for (int t = 0; t < NDT; ++t)
+  for (int t = 0; t < NDT; ++t)
 #pragma unroll
-      for (int gp = 0; gp < 2; ++gp) *reinterpret_cast<u32x4_mem*>(op + t * 32 + 16 * gp) = ow[t][gp];
+    for (int gp = 0; gp < 2; ++gp) {
+      const int ch = 4 * t + 2 * gp + h;
+      *(MLT_LDS u32x4*)(uintptr_t)(o_lds + lq * ROWB + ((ch ^ (lq & CM)) << 4)) = ow[t][gp];
+    }
+  uint16_t* ob = O + ((int64_t)bh * Sq + q0) * D;
+#pragma unroll
+  for (int i = 0; i < 32 / L::RPB; ++i) {
+    const int r = i * L::RPB + lane / L::CPR, cc = lane % L::CPR;
+    const u32x4 v = *(const MLT_LDS u32x4*)(uintptr_t)(o_lds + r * ROWB + ((cc ^ (r & CM)) << 4));
+    if (q0 + r < Sq) *reinterpret_cast<u32x4_mem*>(ob + (int64_t)r * D + cc * 8) = v;
   }
 }
 
