@@ -28,8 +28,8 @@ MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16: 256 CUs x 2.4 GHz x
 # runs summarised under profiles/ (counter x the factor a plain copy of known size gives).
 # Keyed by kernel variant; None when a variant has not been measured.
 MEASURED_TRAFFIC_BYTES = {
-    "mha_fwd_d128_256x64_pp": int((2.0 * 196674 + 131072) * 1024),
-    "gemm_nn_256x256x64_w2x4_pp16": int((2.0 * 786643 + 132403) * 1024),
+    "mha_fwd_d128_256x64_pp": int((2.0 * 196680 + 131072) * 1024),
+    "gemm_nn_256x256x64_w2x4_pp16": int((2.0 * 786569 + 133228) * 1024),
 }
 GEMM_MNK = (8192, 8192, 8192)
 MHA_SHAPE = (4, 32, 4096, 4096, 128)   # B, H, Sq, Sk, D
