@@ -336,6 +336,35 @@ __global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
   // ---- epilogue: fp32 -> 16-bit (RNE), guarded element stores
   const int row_base = m0 + wm * (BM / WM) + 4 * (lane >> 5);
   const int col_base = n0 + wn * (BN / WN) + (lane & 31);
+  // Plain 16-bit store with even N and ldc: neighbouring lanes (columns c, c+1 of the same rows)
+  // exchange two of every four values, so that the even lane holds rows 0, 1 and the odd lane
+  // rows 2, 3 of both columns of a register group: 32-bit stores, half as many.
+  if (epi == 0 && bias == nullptr && !(N & 1) && !(ldc & 1) && !(reinterpret_cast<uintptr_t>(C) & 3)) {
+    const bool odd = lane & 1;
+    auto neighbour = [](float x) {                        // the value lane l ^ 1 passes in
+      return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+    };
+    const int col0 = col_base - (odd ? 1 : 0);
+#pragma unroll
+    for (int i = 0; i < Cfg::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < Cfg::TN; ++j) {
+        const int col = col0 + j * 32;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float got0 = neighbour(odd ? acc[i][j][4 * g] : acc[i][j][4 * g + 2]);
+          const float got1 = neighbour(odd ? acc[i][j][4 * g + 1] : acc[i][j][4 * g + 3]);
+          const uint32_t w0 = odd ? Elem<Tag>::pack2(got0, acc[i][j][4 * g + 2]) : Elem<Tag>::pack2(acc[i][j][4 * g], got0);
+          const uint32_t w1 = odd ? Elem<Tag>::pack2(got1, acc[i][j][4 * g + 3]) : Elem<Tag>::pack2(acc[i][j][4 * g + 1], got1);
+          const int row = row_base + i * 32 + 8 * g + (odd ? 2 : 0);
+          if (col < N) {
+            if (row < M) *reinterpret_cast<uint32_t*>(C + (int64_t)row * ldc + col) = w0;
+            if (row + 1 < M) *reinterpret_cast<uint32_t*>(C + (int64_t)(row + 1) * ldc + col) = w1;
+          }
+        }
+      }
+    return;
+  }
   gemm_epilogue<Tag>([&](auto&& out) {
 #pragma unroll
     for (int i = 0; i < Cfg::TM; ++i)
