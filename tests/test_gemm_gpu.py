@@ -175,6 +175,10 @@ def test_odd_shapes(shape, transB):
 def test_padded_leading_dimensions(transB):
     K, N = 200, 264
     _go(300, N, K, BF16, transB, seed=4, lda=K + 8, ldb=(K if transB else N) + 16, ldc_pad=5)
+    # an even ldc keeps the paired 32-bit stores of the tile kernels: odd M, padding must stay untouched
+    for variant in ("128w8", "64k4", "256"):
+        _go(301, N, K, FP16, transB, seed=4, lda=K + 8, ldb=(K if transB else N) + 16, ldc_pad=6, variant=variant)
+    os.environ.pop("MLT_GEMM_VARIANT", None)
     # unaligned leading dimensions must fall back to the general kernel and still be right
     name, _ = _go(70, N, K, BF16, transB, seed=4, lda=K + 3, ldb=(K if transB else N) + 1, ldc_pad=1)
     assert "general" in name
