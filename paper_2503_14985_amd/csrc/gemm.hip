@@ -501,21 +501,17 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   // Taller A goes to the tile kernels below, which stage A through LDS once per tile: from three
   // row tiles on they are faster (64 x 28672 x 8192: 92-103 us against 108 us for the 64-column
   // streaming form and 177 us for the 16-column one; 64 x 14336 x 4096: 20 us against 28 / 43 us).
-  // The 64-column streaming form stays selectable (MLT_GEMM_VARIANT=skinnydmaw).
   const bool big_b = g.N * g.K >= ((int64_t)1 << 25);
   const bool skinny_auto = g.forced == GEMM_AUTO && g.M <= 32;
-  const bool want_wide = g.forced == GEMM_SKINNY_DMAW;
-  const bool want_narrow = g.forced == GEMM_SKINNY_DMA || (skinny_auto && big_b);
-  if ((want_wide || want_narrow) && gemm_skinny_dma_ok(g)) {
-    p.variant = want_wide ? GEMM_SKINNY_DMAW : GEMM_SKINNY_DMA;
-    p.name = want_wide ? "gemm_nt_skinny_64cols_stream" : "gemm_nt_skinny_16cols_stream";
-    p.bm = (int)((g.M + 15) / 16) * 16; p.bn = want_wide ? 64 : 16; p.bk = want_wide ? 128 : 512;
+  if ((g.forced == GEMM_SKINNY_DMA || (skinny_auto && big_b)) && gemm_skinny_dma_ok(g)) {
+    p.variant = GEMM_SKINNY_DMA;
+    p.name = "gemm_nt_skinny_16cols_stream";
+    p.bm = (int)((g.M + 15) / 16) * 16; p.bn = 16; p.bk = 512;
     p.wm = 1; p.wn = 1;
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
     return p;
   }
-  if ((skinny_auto || g.forced == GEMM_SKINNY || g.forced == GEMM_SKINNY_DMA ||
-       g.forced == GEMM_SKINNY_DMAW) && gemm_skinny_ok(g)) {
+  if ((skinny_auto || g.forced == GEMM_SKINNY || g.forced == GEMM_SKINNY_DMA) && gemm_skinny_ok(g)) {
     p.variant = GEMM_SKINNY; p.name = "gemm_nt_skinny_16cols_ksplit8";
     p.bm = (int)((g.M + 15) / 16) * 16; p.bn = 16; p.bk = 32; p.wm = 1; p.wn = 1;
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
@@ -545,9 +541,9 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     if (cost < best) { best = cost; v = c.variant; }
   }
   if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS && g.forced != GEMM_SKINNY &&
-      g.forced != GEMM_SKINNY_DMA && g.forced != GEMM_SKINNY_DMAW)
+      g.forced != GEMM_SKINNY_DMA)
     v = g.forced;
-  if ((v == GEMM_256_PP || v == GEMM_256_PP16 || v == GEMM_256_W4) && !gemm_pp_ok(g)) v = GEMM_256_W8;
+  if ((v == GEMM_256_PP16 || v == GEMM_256_W4) && !gemm_pp_ok(g)) v = GEMM_256_W8;
   p.variant = v;
   p.bk = 64;
   switch (v) {
@@ -555,10 +551,6 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       p.name = g.transB ? "gemm_nt_256x256x64_w2x2" : "gemm_nn_256x256x64_w2x2"; break;
     case GEMM_256_W8: p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x4" : "gemm_nn_256x256x64_w2x4"; break;
-    case GEMM_256_W8T: p.bm = p.bn = 256; p.wm = 4; p.wn = 2;
-      p.name = g.transB ? "gemm_nt_256x256x64_w4x2" : "gemm_nn_256x256x64_w4x2"; break;
-    case GEMM_256_PP: p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
-      p.name = g.transB ? "gemm_nt_256x256x64_w2x4_pp" : "gemm_nn_256x256x64_w2x4_pp"; break;
     case GEMM_256_W8X1: p.bm = p.bn = 256; p.wm = 8; p.wn = 1;
       p.name = g.transB ? "gemm_nt_256x256x64_w8x1" : "gemm_nn_256x256x64_w8x1"; break;
     case GEMM_256_W1X8: p.bm = p.bn = 256; p.wm = 1; p.wn = 8;
@@ -580,8 +572,8 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       p.name = g.transB ? "gemm_nt_64x128x64_w2x4_k2" : "gemm_nn_64x128x64_w2x4_k2"; break;
     case GEMM_64_K4: p.bm = p.bn = 64; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_64x64x64_w2x2_k4" : "gemm_nn_64x64x64_w2x2_k4"; break;
-    default: p.bm = p.bn = 128; p.wm = 2; p.wn = 2;
-      p.name = g.transB ? "gemm_nt_128x128x64_w2x2" : "gemm_nn_128x128x64_w2x2"; break;
+    default: p.variant = GEMM_256_W8; p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
+      p.name = g.transB ? "gemm_nt_256x256x64_w2x4" : "gemm_nn_256x256x64_w2x4"; break;
   }
   return p;
 }
@@ -607,22 +599,18 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_GENERAL: return launch_general<Tag>(g, s);
     case GEMM_256: return launch_tile_tb<Tag, 256, 256, 64, 2, 2>(g, s);
     case GEMM_256_W8: return launch_tile_tb<Tag, 256, 256, 64, 2, 4>(g, s);
-    case GEMM_256_W8T: return launch_tile_tb<Tag, 256, 256, 64, 4, 2>(g, s);
     case GEMM_256_W8X1: return launch_tile_tb<Tag, 256, 256, 64, 8, 1>(g, s);
     case GEMM_256_W1X8: return launch_tile_tb<Tag, 256, 256, 64, 1, 8>(g, s);
-    case GEMM_128: return launch_tile_tb<Tag, 128, 128, 64, 2, 2>(g, s);
     case GEMM_128_W8: return launch_tile_tb<Tag, 128, 128, 64, 2, 4>(g, s);
     case GEMM_64X128_W8: return launch_tile_tb<Tag, 64, 128, 64, 2, 4>(g, s);
     case GEMM_64_W4: return launch_tile_tb<Tag, 64, 64, 64, 2, 2>(g, s);
     case GEMM_128_K2: return launch_tile_tb<Tag, 128, 128, 64, 2, 4, 2>(g, s);
     case GEMM_64X128_K2: return launch_tile_tb<Tag, 64, 128, 64, 2, 4, 2>(g, s);
     case GEMM_64_K4: return launch_tile_tb<Tag, 64, 64, 64, 2, 2, 4, 3>(g, s);
-    case GEMM_256_PP: return run_gemm_pp(g, 32, s);
-    case GEMM_256_PP16: return run_gemm_pp(g, 16, s);
+    case GEMM_256_PP16: return run_gemm_pp(g, s);
     case GEMM_256_W4: return run_gemm_w4(g, s);
     case GEMM_SKINNY: return run_gemm_skinny(g, s);
-    case GEMM_SKINNY_DMA: return run_gemm_skinny_dma(g, false, s);
-    case GEMM_SKINNY_DMAW: return run_gemm_skinny_dma(g, true, s);
+    case GEMM_SKINNY_DMA: return run_gemm_skinny_dma(g, s);
   }
   return MLT_ERR_UNSUPPORTED;
 }

@@ -387,15 +387,14 @@ static int launch_pp(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
-template <int MS>
-static int run_gemm_pp_ms(const GemmArgs& g, hipStream_t s) {
+// Only the 16x16x32 form is instantiated (MS = 16): measured on N(0,1) operands it runs 8-17 %
+// faster than the 32x32x16 form of the same schedule (the chip is power-limited and this MFMA
+// shape moves half as many accumulator registers per flop).
+int run_gemm_pp(const GemmArgs& g, hipStream_t s) {
+  constexpr int MS = 16;
   if (g.dtype == MLT_BF16)
     return g.transB ? launch_pp<bf16_tag, true, MS>(g, s) : launch_pp<bf16_tag, false, MS>(g, s);
   return g.transB ? launch_pp<f16_tag, true, MS>(g, s) : launch_pp<f16_tag, false, MS>(g, s);
-}
-
-int run_gemm_pp(const GemmArgs& g, int mfma_size, hipStream_t s) {
-  return mfma_size == 16 ? run_gemm_pp_ms<16>(g, s) : run_gemm_pp_ms<32>(g, s);
 }
 
 }  // namespace mlt

@@ -150,11 +150,10 @@ int run_skinny_t(const GemmArgs& g, hipStream_t s) {
 // is the shape of its HBM requests (one load instruction touches 16 rows with 64 bytes each) and,
 // for taller A, that A is fetched from L2 again for every 16 columns. Here B goes through an LDS
 // ring in long contiguous row pieces and stays 7 stages (112 KB per CU) in flight:
-//   * a stage is 16 KB of B: in the narrow form 16 rows x 512 k (1 KB per row, one row per load
-//     instruction: 64 lanes x 16 contiguous bytes, global_load_lds_dwordx4), in the wide form
-//     64 rows x 128 k (256 bytes per row, four rows per load instruction). The narrow form has
-//     the better request shape; the wide form reuses every A fragment for four column tiles, which
-//     matters once A has more than one 16-row tile. The ring holds 8 stages (128 KB);
+//   * a stage is 16 KB of B: 16 rows x 512 k (1 KB per row, one row per load instruction: 64 lanes
+//     x 16 contiguous bytes, global_load_lds_dwordx4). (A wider stage of 64 rows x 128 k, which
+//     reuses every A fragment for four column tiles, measured slower than the small-tile kernels
+//     wherever it beat this one, and is no longer built.) The ring holds 8 stages (128 KB);
 //   * wavefronts 0-3 only fetch: wavefront p issues load instructions 4p .. 4p+3 of every stage,
 //     seven stages ahead. Their vector-memory counter sees nothing but these loads, so "stage s
 //     has landed" is an exact count; wavefronts 4-7 only compute: they split the 32-wide k chunks
@@ -172,9 +171,9 @@ constexpr int SD_STAGE_B = 16384;     // bytes of B per stage
 constexpr int SD_SMEM = SD_ST * SD_STAGE_B;
 constexpr int SD_RED = 4 * 4 * 256 * 4;   // reduction area behind the ring: [4 wavefronts][4 tiles][256]
 
-template <bool WIDE> struct SdCfg {
-  static constexpr int RPS = WIDE ? 64 : 16;     // rows of B (columns of C) per stage and column block
-  static constexpr int KS = WIDE ? 128 : 512;    // k values per stage
+struct SdCfg {
+  static constexpr int RPS = 16;                 // rows of B (columns of C) per stage and column block
+  static constexpr int KS = 512;                 // k values per stage
   static constexpr int PB = KS * 2;              // bytes of a row piece
   static constexpr int LPR = PB / 16;            // lanes per row piece
   static constexpr int NT = RPS / 16;            // 16-column tiles per block
@@ -190,12 +189,12 @@ __device__ __forceinline__ void sd_load_lds16(const void* base, uint32_t voff, u
                : "memory", "m0");
 }
 
-template <typename Tag, int MT, bool WIDE>
+template <typename Tag, int MT>
 __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc) {
   typedef typename Elem<Tag>::vec8 V8;
-  typedef SdCfg<WIDE> L;
+  typedef SdCfg L;
   constexpr int KS = L::KS, NT = L::NT, J = L::J;
   extern __shared__ __align__(16) char smem[];             // the ring, then the reduction area
   const int tid = threadIdx.x, lane = tid & 63;
@@ -209,7 +208,7 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
   // instead of once per block. All stages of all groups form one stream g = 0 .. G-1, so the ring
   // never drains between blocks or groups.
   // (as many as the registers take: 8 blocks for one 16-row tile of A in the narrow form)
-  constexpr int GB = WIDE ? 2 : (MT == 1 ? 8 : MT == 2 ? 4 : 2);
+  constexpr int GB = MT == 1 ? 8 : MT == 2 ? 4 : 2;
   const int nmine = (nblocks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
   const int G = nmine * NS;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
@@ -383,9 +382,9 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
   }
 }
 
-template <typename Tag, int MT, bool WIDE>
+template <typename Tag, int MT>
 int launch_skinny_dma(const GemmArgs& g, hipStream_t s) {
-  auto kern = gemm_skinny_dma_kernel<Tag, MT, WIDE>;
+  auto kern = gemm_skinny_dma_kernel<Tag, MT>;
   static thread_local int configured_dev = -1;            // opt in to > 64 KB LDS once per device
   static thread_local int ncu = 0;
   int dev = 0;
@@ -399,20 +398,20 @@ int launch_skinny_dma(const GemmArgs& g, hipStream_t s) {
     }
     configured_dev = dev;
   }
-  const int64_t nblocks = (g.N + SdCfg<WIDE>::RPS - 1) / SdCfg<WIDE>::RPS;
+  const int64_t nblocks = (g.N + SdCfg::RPS - 1) / SdCfg::RPS;
   const unsigned nwg = (unsigned)(nblocks < ncu ? nblocks : ncu);   // one persistent workgroup per CU
   hipLaunchKernelGGL(kern, dim3(nwg), dim3(SK_NT), SD_SMEM + SD_RED, s, (int)g.M, (int)g.N, (int)g.K,
                      g.A, g.lda, g.B, g.ldb, g.C, g.ldc);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
-template <typename Tag, bool WIDE>
+template <typename Tag>
 int run_skinny_dma_t(const GemmArgs& g, hipStream_t s) {
   switch ((g.M + 15) / 16) {
-    case 1: return launch_skinny_dma<Tag, 1, WIDE>(g, s);
-    case 2: return launch_skinny_dma<Tag, 2, WIDE>(g, s);
-    case 3: return launch_skinny_dma<Tag, 3, WIDE>(g, s);
-    case 4: return launch_skinny_dma<Tag, 4, WIDE>(g, s);
+    case 1: return launch_skinny_dma<Tag, 1>(g, s);
+    case 2: return launch_skinny_dma<Tag, 2>(g, s);
+    case 3: return launch_skinny_dma<Tag, 3>(g, s);
+    case 4: return launch_skinny_dma<Tag, 4>(g, s);
   }
   return MLT_ERR_UNSUPPORTED;
 }
@@ -437,10 +436,8 @@ bool gemm_skinny_dma_ok(const GemmArgs& g) {
   return gemm_skinny_ok(g) && g.ldb * 2 * 64 + g.K * 2 < ((int64_t)1 << 32);
 }
 
-int run_gemm_skinny_dma(const GemmArgs& g, bool wide, hipStream_t s) {
-  if (wide)
-    return g.dtype == MLT_BF16 ? run_skinny_dma_t<bf16_tag, true>(g, s) : run_skinny_dma_t<f16_tag, true>(g, s);
-  return g.dtype == MLT_BF16 ? run_skinny_dma_t<bf16_tag, false>(g, s) : run_skinny_dma_t<f16_tag, false>(g, s);
+int run_gemm_skinny_dma(const GemmArgs& g, hipStream_t s) {
+  return g.dtype == MLT_BF16 ? run_skinny_dma_t<bf16_tag>(g, s) : run_skinny_dma_t<f16_tag>(g, s);
 }
 
 }  // namespace mlt

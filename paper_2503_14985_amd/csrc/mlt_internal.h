@@ -8,16 +8,12 @@ namespace mlt {
 
 enum GemmVariant {
   GEMM_AUTO = -1, GEMM_ZERO = 0, GEMM_GENERAL = 1,
-  GEMM_256 = 2,       // 256x256x64, 4 wavefronts (2x2) of 128x128
-  GEMM_128 = 3,       // 128x128x64, 4 wavefronts (2x2) of 64x64
-  GEMM_256_W8 = 4,    // 256x256x64, 8 wavefronts (2x4) of 128x64
-  GEMM_256_W8T = 5,   // 256x256x64, 8 wavefronts (4x2) of 64x128
-  GEMM_256_PP = 6,    // 256x256x64, 8 wavefronts (2x4), two-group schedule, direct-to-LDS loads
+  GEMM_256 = 2,       // 256x256x64, 4 wavefronts (2x2) of 128x128 (tiling hint "square" with a ragged K)
+  GEMM_256_W8 = 4,    // 256x256x64, 8 wavefronts (2x4) of 128x64 (big tiles when the direct loads do not apply)
   GEMM_SKINNY = 7,    // M <= 64, B stored N x K: 16 columns per workgroup, K split over 8 wavefronts
   GEMM_SKINNY_DMA = 8,  // same shapes, B streamed through an LDS ring: 16 columns x 512 k per stage
-  GEMM_SKINNY_DMAW = 9, // the same with 64 columns x 128 k per stage
   GEMM_256_W4 = 10,   // 256x256x64, 4 wavefronts (2x2) of 128x128, software-pipelined, direct-to-LDS loads
-  GEMM_256_PP16 = 11, // the two-group kernel on 16x16x32 MFMAs
+  GEMM_256_PP16 = 11, // 256x256x64, 8 wavefronts (2x4), two-group schedule, direct-to-LDS loads, 16x16x32 MFMAs
   GEMM_256_W8X1 = 12, // 256x256x64, 8 wavefronts as 8x1: row strips of 32 x 256 ("horizontal")
   GEMM_256_W1X8 = 13, // 256x256x64, 8 wavefronts as 1x8: column strips of 256 x 32 ("vertical")
   GEMM_128_W8 = 14,   // 128x128x64, 8 wavefronts (2x4) of 64x32
@@ -53,12 +49,20 @@ struct GemmPlan {
 GemmPlan plan_gemm(const GemmArgs& g);
 int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s);
 bool gemm_pp_ok(const GemmArgs& g);            // gemm_pp.hip: can the two-group kernel take this problem?
-int run_gemm_pp(const GemmArgs& g, int mfma_size, hipStream_t s);   // mfma_size 32: 32x32x16, 16: 16x16x32
+int run_gemm_pp(const GemmArgs& g, hipStream_t s);
 int run_gemm_w4(const GemmArgs& g, hipStream_t s);   // gemm_w4.hip; same operand requirements (gemm_pp_ok)
 bool gemm_skinny_ok(const GemmArgs& g);        // gemm_skinny.hip
 int run_gemm_skinny(const GemmArgs& g, hipStream_t s);
 bool gemm_skinny_dma_ok(const GemmArgs& g);
-int run_gemm_skinny_dma(const GemmArgs& g, bool wide, hipStream_t s);
+int run_gemm_skinny_dma(const GemmArgs& g, hipStream_t s);
+
+enum MhaVariant {
+  MHA_AUTO = -1,
+  MHA_PP32 = 0,   // two-group kernel, 32x32x16 MFMAs, one workgroup per (batch*head, query tile)
+  MHA_PP16 = 1,   // the same on 16x16x32 MFMAs
+  MHA_PS = 2,     // persistent form of the two-group kernel (unmasked, D = 128, at least two key tiles)
+  MHA_NUM_VARIANTS
+};
 
 struct MhaArgs {
   int64_t B, H, Sq, Sk, D;
@@ -66,20 +70,30 @@ struct MhaArgs {
   uint16_t* O;
   float scale;
   int causal, dtype;
+  int forced = MHA_AUTO;   // MhaVariant or MHA_AUTO
+  int ps_grid = 0;         // persistent kernel: number of workgroups (0: one per CU)
 };
 
 struct MhaPlan {
   const char* name = "";
   int bm = 0, bn = 0, waves = 0;
   bool supported = false;
-  bool two_group = false;   // mha_pp.hip (default) or the single-schedule kernel of mha.hip
-  int mfma_size = 32;       // two-group kernel: 32 = 32x32x16 MFMAs, 16 = 16x16x32
-  bool persistent = false;  // two-group kernel, one workgroup per CU walking through the items
+  int mfma_size = 32;       // 32 = 32x32x16 MFMAs, 16 = 16x16x32
+  bool persistent = false;  // one workgroup per CU walking through the items
 };
 bool mha_pp_ok(const MhaArgs& a);
 int run_mha_pp(const MhaArgs& a, int mfma_size, hipStream_t s);
 bool mha_ps_ok(const MhaArgs& a);              // mha_pp.hip: can the persistent kernel take this problem?
 int run_mha_ps(const MhaArgs& a, hipStream_t s);
+
+// Process-wide overrides of the automatic kernel choice, for tuning and for the tests that must
+// reach every kernel (mlt_diag_force_variant; initial values from MLT_GEMM_VARIANT /
+// MLT_MHA_VARIANT / MLT_MHA_PS_GRID, read once).
+struct Overrides { int gemm = GEMM_AUTO; int mha = MHA_AUTO; int ps_grid = 0; };
+Overrides& overrides();
+// Device facts the launchers need, cached per thread for the current device.
+struct DeviceInfo { int ncu = 0; bool gfx950 = false; };
+bool device_info(DeviceInfo& out);
 
 // probe.hip: launches the register-only MFMA loop, returns the flop it will execute (< 0: launch failed)
 double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, int mfma_size, hipStream_t s);
