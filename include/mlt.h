@@ -109,9 +109,10 @@ int mlt_gemm_bias_act(int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
  *   causal != 0: key j is visible to query i iff j <= i (lower triangle including the
  *                diagonal, aligned at the top-left corner; key 0 is visible to every query).
  *
- * D must be 64 or 128 (else MLT_ERR_UNSUPPORTED). B, H or Sq equal to 0 is a no-op. Sk must be
- * >= 1 (a softmax over no keys is undefined: MLT_ERR_INVALID_ARG). All four base pointers must
- * be 16-byte aligned and scale must be finite (MLT_ERR_INVALID_ARG otherwise).
+ * D must be 64 or 128 and one head's K must stay below 2 GiB (Sk * D * 2 < 2^31), else
+ * MLT_ERR_UNSUPPORTED. B, H or Sq equal to 0 is a no-op. Sk must be >= 1 (a softmax over no keys
+ * is undefined: MLT_ERR_INVALID_ARG). All four base pointers must be 16-byte aligned and scale
+ * must be finite (MLT_ERR_INVALID_ARG otherwise).
  */
 int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const void* Q,
                 const void* K, const void* V, void* O, float scale, int causal, int dtype,
@@ -129,7 +130,9 @@ int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const v
  *   block_table   device, int32 [B, max_blocks]: physical block of logical block i of sequence b;
  *                 logical key p is slot p % block_size of block block_table[b][p / block_size]
  *   seq_lens      device, int32 [B], 1 <= seq_lens[b] <= max_blocks * block_size
- * Table entries and cache slots past seq_lens[b] are never read. The library cannot inspect
+ * Table entries past the last used block are never read; cache slots are read in units of 16
+ * keys, so the slots from seq_lens[b] up to the next multiple of 16 inside the last used block are
+ * read and ignored (their weights are forced to zero), nothing beyond them. The library cannot inspect
  * device data: an entry outside [0, num_blocks) or a length outside its range is CLAMPED into it
  * (wrong result for that sequence, no out-of-range access).
  * D must be 64 or 128, block_size a multiple of 16 up to 1024 (else MLT_ERR_UNSUPPORTED); Q, Kc
@@ -139,64 +142,6 @@ int mlt_paged_attn_decode(int64_t B, int64_t H, int64_t D, int64_t block_size, i
                           int64_t num_blocks, const void* Q, const void* Kc, const void* Vc,
                           const int32_t* block_table, const int32_t* seq_lens, void* O,
                           float scale, int dtype, void* stream);
-
-/*
- * Diagnostic for benchmarks (not part of the paper's method): enqueues one kernel in which every
- * wavefront of the chip issues bf16 32x32x16 MFMAs back to back from registers, `iters` times 32
- * of them, 8 wavefronts per CU. The rate it reaches is the practical MFMA ceiling FOR THE GIVEN
- * OPERAND VALUES: the chip lowers its clock under the power that toggling operand bits costs.
- *   data    device, at least 64 KiB, 16-byte aligned: the bf16 values used as operands
- *   sink    device, at least 4 bytes (written practically never; keeps the loop alive)
- *   flop    host, out: floating-point operations the launch executes (time it with events)
- * Returns MLT_OK, MLT_ERR_INVALID_ARG (null pointer, iters outside 1 .. 2^20) or a launch/device
- * error.
- */
-int mlt_probe_mfma(int iters, const void* data, void* sink, double* flop, void* stream);
-
-/*
- * The same diagnostic on 16x16x32 MFMAs (64 per iteration and wavefront, the same flop count):
- * the shape the big-tile GEMM uses. On N(0,1) operands the chip sustains a higher rate of these
- * than of 32x32x16 MFMAs (it is power-limited, and this shape reads and writes half as many
- * accumulator registers per flop). Arguments and return values as for mlt_probe_mfma.
- */
-int mlt_probe_mfma16(int iters, const void* data, void* sink, double* flop, void* stream);
-
-/*
- * Diagnostic for benchmarks (not part of the paper's method): enqueues one kernel that reads
- * `bytes` bytes at `data` once with 16-byte loads from every CU and writes nothing. On a buffer
- * much larger than the caches its duration gives the practical HBM read rate, the ceiling for
- * the memory-bound kernels here (paged-attention decode, skinny GEMM).
- *   data    device, 16-byte aligned, `bytes` bytes (a positive multiple of 16); only read
- *   sink    device, at least 4 bytes (never written in practice; keeps the loads alive)
- * Returns MLT_OK, MLT_ERR_INVALID_ARG (null pointer, bad size or alignment) or a launch/device
- * error.
- */
-int mlt_probe_hbm_read(const void* data, int64_t bytes, void* sink, void* stream);
-
-/*
- * Per-kernel timing hook for benchmarks: when `start_event`/`stop_event` (hipEvent_t as void*,
- * may be NULL) are set, the next launches made by this thread record them on the launch stream
- * immediately before the first and after the last kernel of one entry-point call. Pass NULLs to
- * switch it off. Host-side state only; thread-local.
- */
-void mlt_set_timing_events(void* start_event, void* stop_event);
-
-/*
- * Name of the kernel variant the last successful call on this thread selected (static string,
- * e.g. "gemm_bf16_nn_256x256x64"); "" before any call. For logs and profiles.
- */
-const char* mlt_last_kernel(void);
-
-/*
- * Host-only query of the tiling a call would use, mirroring the paper's layout encoding
- * (Section 2.1: sizePerWarp and warpsPerCTA of the root operation). Fills
- *   out[0..1] workgroup tile (rows, cols), out[2..3] wavefronts per workgroup (rows, cols),
- *   out[4..5] sub-tile per wavefront, out[6..8] MFMA tile (m, n, k), out[9] K step (GEMM) or key
- *   tile (attention).
- * `op` 0 = GEMM (dims = M, N, K, transB), 1 = attention (dims = Sq, Sk, D, causal).
- * Returns MLT_OK or an error as the compute call would.
- */
-int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]);
 
 /* Static, human-readable text for a status code. */
 const char* mlt_status_string(int status);

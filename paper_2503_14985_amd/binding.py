@@ -18,13 +18,16 @@ LIB_PATH = os.path.join(_HERE, "libmlt.so")
 MLT_BF16, MLT_FP16 = 0, 1
 MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE = 0, -1, -2, -3, -4
 
-EXPORTS = ("mlt_gemm", "mlt_mha_fwd", "mlt_set_timing_events", "mlt_last_kernel",
-           "mlt_query_tiling", "mlt_status_string", "mlt_version", "mlt_probe_mfma",
-           "mlt_paged_attn_decode", "mlt_gemm_acc", "mlt_probe_hbm_read", "mlt_gemm_bias_act", "mlt_probe_mfma16", "mlt_gemm_tiled")
+# include/mlt.h (the operations) and include/mlt_diag.h (probes, timing hooks, kernel-choice overrides)
+EXPORTS = ("mlt_gemm", "mlt_gemm_acc", "mlt_gemm_tiled", "mlt_gemm_bias_act", "mlt_mha_fwd",
+           "mlt_paged_attn_decode", "mlt_status_string", "mlt_version")
+DIAG_EXPORTS = ("mlt_probe_mfma", "mlt_probe_mfma16", "mlt_probe_hbm_read", "mlt_set_timing_events",
+                "mlt_last_kernel", "mlt_query_tiling", "mlt_diag_force_variant",
+                "mlt_diag_force_k_parts", "mlt_diag_set_persistent_grid")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
-        "libmlt.so is not built (%s). Run `python -c 'import __graft_entry__ as g; g.build()'` "
+        "libmlt.so is not built (%s). Run `python -c 'import __graft_entry__ as g; g.build_lib()'` "
         "from the repository root; there is no CPU fallback." % LIB_PATH)
 
 _lib = ctypes.CDLL(LIB_PATH)
@@ -54,6 +57,12 @@ _lib.mlt_set_timing_events.argtypes = [_p, _p]
 _lib.mlt_last_kernel.restype = ctypes.c_char_p
 _lib.mlt_query_tiling.restype = _i32
 _lib.mlt_query_tiling.argtypes = [_i32, ctypes.POINTER(_i64), _i32, ctypes.POINTER(ctypes.c_int32)]
+_lib.mlt_diag_force_variant.restype = _i32
+_lib.mlt_diag_force_variant.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+_lib.mlt_diag_force_k_parts.restype = _i32
+_lib.mlt_diag_force_k_parts.argtypes = [_i32]
+_lib.mlt_diag_set_persistent_grid.restype = _i32
+_lib.mlt_diag_set_persistent_grid.argtypes = [_i32]
 _lib.mlt_status_string.restype = ctypes.c_char_p
 _lib.mlt_status_string.argtypes = [_i32]
 _lib.mlt_version.restype = ctypes.c_char_p
@@ -80,6 +89,28 @@ def mlt_version() -> str:
 
 def mlt_last_kernel() -> str:
     return _lib.mlt_last_kernel().decode()
+
+
+def mlt_diag_force_variant(gemm: str | None = None, mha: str | None = None) -> None:
+    """Force a GEMM and/or attention kernel variant for the whole process (None: leave as is,
+    "auto": the library's own choice)."""
+    rc = _lib.mlt_diag_force_variant(None if gemm is None else gemm.encode(),
+                                     None if mha is None else mha.encode())
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_diag_force_variant")
+
+
+def mlt_diag_force_k_parts(parts: int) -> None:
+    """0: the library's choice; 1: no K split across workgroups; 2 / 4 / 8: that many parts."""
+    rc = _lib.mlt_diag_force_k_parts(int(parts))
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_diag_force_k_parts")
+
+
+def mlt_diag_set_persistent_grid(workgroups: int) -> None:
+    rc = _lib.mlt_diag_set_persistent_grid(int(workgroups))
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_diag_set_persistent_grid")
 
 
 def mlt_paged_attn_decode(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
@@ -179,13 +210,11 @@ def _rows_contiguous(t: torch.Tensor, name: str) -> int:
     return t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
 
 
-def mlt_gemm(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor | None = None, transB: bool = False,
-             stream=None) -> torch.Tensor:
-    """C = A @ B (transB=False, B is [K, N]) or C = A @ B.T (transB=True, B is [N, K]).
-
-    Row strides of A, B and C are passed through as lda/ldb/ldc, so row-sliced views work."""
-    if not (A.is_cuda and B.is_cuda):
-        raise ValueError("mlt_gemm needs GPU tensors")
+def _gemm_operands(name: str, A, B, C, transB: bool, c_dtype=None):
+    """Shapes, dtype code and leading dimensions of a GEMM call (C allocated when None): the
+    marshalling every GEMM entry point shares."""
+    if not (A.is_cuda and B.is_cuda and (C is None or C.is_cuda)):
+        raise ValueError("%s needs GPU tensors" % name)
     dt = _dtype_code(A)
     if B.dtype != A.dtype:
         raise TypeError("A and B must share a dtype")
@@ -193,11 +222,21 @@ def mlt_gemm(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor | None = None, tr
     N, Kb = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
     if K != Kb:
         raise ValueError("inner dimensions differ: %d vs %d" % (K, Kb))
+    c_dtype = A.dtype if c_dtype is None else c_dtype
     if C is None:
-        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
-    elif C.dtype != A.dtype or tuple(C.shape) != (M, N):
+        C = torch.empty((M, N), dtype=c_dtype, device=A.device)
+    elif C.dtype != c_dtype or tuple(C.shape) != (M, N):
         raise ValueError("C has the wrong dtype or shape")
     lda, ldb, ldc = _rows_contiguous(A, "A"), _rows_contiguous(B, "B"), _rows_contiguous(C, "C")
+    return M, N, K, lda, ldb, ldc, dt, C
+
+
+def mlt_gemm(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor | None = None, transB: bool = False,
+             stream=None) -> torch.Tensor:
+    """C = A @ B (transB=False, B is [K, N]) or C = A @ B.T (transB=True, B is [N, K]).
+
+    Row strides of A, B and C are passed through as lda/ldb/ldc, so row-sliced views work."""
+    M, N, K, lda, ldb, ldc, dt, C = _gemm_operands("mlt_gemm", A, B, C, transB)
     with torch.cuda.device(A.device):
         rc = _lib.mlt_gemm(M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, int(transB),
                            C.data_ptr(), ldc, dt, _stream(stream))
@@ -213,20 +252,7 @@ TILING_AUTO, TILING_HORIZONTAL, TILING_VERTICAL, TILING_SQUARE = 0, 1, 2, 3
 def mlt_gemm_tiled(A: torch.Tensor, B: torch.Tensor, tiling: int, C: torch.Tensor | None = None,
                    transB: bool = False, stream=None) -> torch.Tensor:
     """mlt_gemm with the paper's tiling hint (TILING_AUTO / _HORIZONTAL / _VERTICAL / _SQUARE)."""
-    if not (A.is_cuda and B.is_cuda):
-        raise ValueError("mlt_gemm_tiled needs GPU tensors")
-    dt = _dtype_code(A)
-    if B.dtype != A.dtype:
-        raise TypeError("A and B must share a dtype")
-    M, K = A.shape
-    N, Kb = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
-    if K != Kb:
-        raise ValueError("inner dimensions differ: %d vs %d" % (K, Kb))
-    if C is None:
-        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
-    elif C.dtype != A.dtype or tuple(C.shape) != (M, N):
-        raise ValueError("C has the wrong dtype or shape")
-    lda, ldb, ldc = _rows_contiguous(A, "A"), _rows_contiguous(B, "B"), _rows_contiguous(C, "C")
+    M, N, K, lda, ldb, ldc, dt, C = _gemm_operands("mlt_gemm_tiled", A, B, C, transB)
     with torch.cuda.device(A.device):
         rc = _lib.mlt_gemm_tiled(M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, int(transB),
                                  C.data_ptr(), ldc, dt, int(tiling), _stream(stream))
@@ -240,23 +266,10 @@ def mlt_gemm_bias_act(A: torch.Tensor, B: torch.Tensor, bias: torch.Tensor | Non
                       stream=None) -> torch.Tensor:
     """C = act(A @ B + bias) (or A @ B.T), bias a contiguous [N] tensor of the input dtype or None,
     act one of ACT_NONE / ACT_RELU / ACT_GELU."""
-    if not (A.is_cuda and B.is_cuda):
-        raise ValueError("mlt_gemm_bias_act needs GPU tensors")
-    dt = _dtype_code(A)
-    if B.dtype != A.dtype:
-        raise TypeError("A and B must share a dtype")
-    M, K = A.shape
-    N, Kb = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
-    if K != Kb:
-        raise ValueError("inner dimensions differ: %d vs %d" % (K, Kb))
+    M, N, K, lda, ldb, ldc, dt, C = _gemm_operands("mlt_gemm_bias_act", A, B, C, transB)
     if bias is not None and (not bias.is_cuda or bias.dtype != A.dtype or tuple(bias.shape) != (N,)
                              or not bias.is_contiguous()):
         raise ValueError("bias must be a contiguous GPU tensor of N elements of the input dtype")
-    if C is None:
-        C = torch.empty((M, N), dtype=A.dtype, device=A.device)
-    elif C.dtype != A.dtype or tuple(C.shape) != (M, N):
-        raise ValueError("C has the wrong dtype or shape")
-    lda, ldb, ldc = _rows_contiguous(A, "A"), _rows_contiguous(B, "B"), _rows_contiguous(C, "C")
     with torch.cuda.device(A.device):
         rc = _lib.mlt_gemm_bias_act(M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, int(transB),
                                     bias.data_ptr() if bias is not None else None, int(act),
@@ -269,18 +282,9 @@ def mlt_gemm_bias_act(A: torch.Tensor, B: torch.Tensor, bias: torch.Tensor | Non
 def mlt_gemm_acc(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor, transB: bool = False,
                  stream=None) -> torch.Tensor:
     """C += A @ B (or A @ B.T) with C an fp32 [M, N] tensor that is read and written."""
-    if not (A.is_cuda and B.is_cuda and C.is_cuda):
-        raise ValueError("mlt_gemm_acc needs GPU tensors")
-    dt = _dtype_code(A)
-    if B.dtype != A.dtype:
-        raise TypeError("A and B must share a dtype")
-    M, K = A.shape
-    N, Kb = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
-    if K != Kb:
-        raise ValueError("inner dimensions differ: %d vs %d" % (K, Kb))
-    if C.dtype != torch.float32 or tuple(C.shape) != (M, N):
-        raise ValueError("C must be an fp32 [M, N] tensor")
-    lda, ldb, ldc = _rows_contiguous(A, "A"), _rows_contiguous(B, "B"), _rows_contiguous(C, "C")
+    if C is None:
+        raise ValueError("mlt_gemm_acc needs the fp32 C it accumulates into")
+    M, N, K, lda, ldb, ldc, dt, C = _gemm_operands("mlt_gemm_acc", A, B, C, transB, torch.float32)
     with torch.cuda.device(A.device):
         rc = _lib.mlt_gemm_acc(M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, int(transB),
                                C.data_ptr(), ldc, dt, _stream(stream))

@@ -11,6 +11,8 @@
 // tiles are staged through LDS: each byte is fetched from global memory once per workgroup and
 // read by the wavefronts that share it (the rows/columns of the warp grid that Section 2.2 notes
 // work on the same sub-block of A or B).
+#include <mutex>
+
 #include "mlt_common.h"
 #include "mlt_internal.h"
 
@@ -73,14 +75,30 @@ struct GemmTile {
   static_assert(BK % 16 == 0 && BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "MFMA tiling");
 };
 
+// K split across workgroups (part_steps > 0): the grid's y index is the part; part p takes the K
+// steps p * part_steps .. of the problem and stores its fp32 partial tile (epi = EPI_PART32) into
+// slice p of the scratch that C_ then points at (slices part_stride floats apart, row stride ldc);
+// gemm_splitk_reduce_kernel adds the slices in a fixed order and applies the real epilogue.
 template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB, int KS>
 __global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
-    int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
-    const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
-    int nbn, int epi, const uint16_t* __restrict__ bias) {
+    int M, int N, int K_, const uint16_t* __restrict__ A_, int64_t lda,
+    const uint16_t* __restrict__ B_, int64_t ldb, uint16_t* __restrict__ C_, int64_t ldc, int nbm,
+    int nbn, int epi, const uint16_t* __restrict__ bias, int part_steps, int64_t part_stride) {
   typedef GemmTile<Tag, BM, BN, BK, WM, WN, TRANSB> Cfg;
   typedef typename Elem<Tag>::vec8 V8;
   extern __shared__ __align__(16) char smem_all[];
+  const uint16_t* A = A_;
+  const uint16_t* B = B_;
+  uint16_t* C = C_;
+  int K = K_;
+  if (part_steps > 0) {
+    const int part = blockIdx.y;
+    const int k_begin = part * part_steps * BK;            // < K_: the host launches no empty part
+    A += k_begin;
+    B += TRANSB ? (int64_t)k_begin : (int64_t)k_begin * ldb;
+    K = K_ - k_begin < part_steps * BK ? K_ - k_begin : part_steps * BK;
+    C = reinterpret_cast<uint16_t*>(reinterpret_cast<float*>(C_) + (int64_t)part * part_stride);
+  }
 
   // KS > 1: the workgroup holds KS groups of WM x WN wavefronts; group kg runs the whole pipeline
   // below on its own LDS stages over its own share of the K steps, and the groups' accumulators
@@ -438,6 +456,34 @@ __global__ __launch_bounds__(256) void gemm_general_kernel(
   }, C, epi, bias);
 }
 
+// Second pass of a K split across workgroups: C = epilogue(sum over parts, in the order 0, 1, ...,
+// of the fp32 partial products). One thread per four consecutive columns of a row.
+template <typename Tag>
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(
+    int M, int N, int parts, const float* __restrict__ ws, int64_t part_stride,
+    uint16_t* __restrict__ C, int64_t ldc, int epi, const uint16_t* __restrict__ bias) {
+  const int nq = (N + 3) / 4;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= (int64_t)M * nq) return;
+  const int row = (int)(t / nq), col0 = (int)(t % nq) * 4;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  const float* src = ws + (int64_t)row * N + col0;
+  if (col0 + 3 < N && (N & 3) == 0) {
+    for (int p = 0; p < parts; ++p) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(src + (int64_t)p * part_stride);
+      acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+    }
+  } else {
+    for (int p = 0; p < parts; ++p)
+      for (int e = 0; e < 4; ++e)
+        if (col0 + e < N) acc[e] += src[(int64_t)p * part_stride + e];
+  }
+  gemm_epilogue<Tag>([&](auto&& out) {
+    for (int e = 0; e < 4; ++e)
+      if (col0 + e < N) out((int64_t)row * ldc + col0 + e, col0 + e, acc[e]);
+  }, C, epi, bias);
+}
+
 // K == 0: the empty sum (only launched when C is overwritten; C += 0 is a no-op).
 __global__ void gemm_zero_kernel(int M, int N, uint16_t* __restrict__ C, int64_t ldc) {
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -464,8 +510,24 @@ static int launch_tile(const GemmArgs& g, hipStream_t s) {
     configured_dev = dev;
   }
   const int nbm = (int)((g.M + BM - 1) / BM), nbn = (int)((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(Cfg::NT * KS), KS * Cfg::SMEM, s, (int)g.M, (int)g.N,
-                     (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.epi(), g.bias);
+  if (g.parts <= 1) {
+    hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(Cfg::NT * KS), KS * Cfg::SMEM, s, (int)g.M, (int)g.N,
+                       (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.epi(), g.bias, 0,
+                       (int64_t)0);
+    return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
+  }
+  // K split across workgroups: fp32 partial tiles into the scratch, then the fixed-order sum
+  const int KT = (int)((g.K + BK - 1) / BK);
+  const int part_steps = (KT + g.parts - 1) / g.parts;
+  const int parts = (KT + part_steps - 1) / part_steps;    // no empty part
+  const int64_t part_stride = g.M * g.N;
+  hipLaunchKernelGGL(kern, dim3(nbm * nbn, parts), dim3(Cfg::NT * KS), KS * Cfg::SMEM, s, (int)g.M,
+                     (int)g.N, (int)g.K, g.A, g.lda, g.B, g.ldb, reinterpret_cast<uint16_t*>(g.scratch),
+                     g.N, nbm, nbn, (int)EPI_PART32, (const uint16_t*)nullptr, part_steps, part_stride);
+  if (hipGetLastError() != hipSuccess) return MLT_ERR_LAUNCH;
+  const int64_t nthreads = g.M * ((g.N + 3) / 4);
+  hipLaunchKernelGGL(gemm_splitk_reduce_kernel<Tag>, dim3((unsigned)((nthreads + 255) / 256)), dim3(256),
+                     0, s, (int)g.M, (int)g.N, parts, g.scratch, part_stride, g.C, g.ldc, g.epi(), g.bias);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
@@ -495,14 +557,82 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.bm = 64; p.bn = 64; p.bk = 32; p.wm = 2; p.wn = 2;
     return p;
   }
-  // Skinny kernels (B stored N x K, no LDS staging of A): the automatic choice for one or two
-  // 16-row tiles of A; B streamed through an LDS ring (16 columns x 512 k per stage, the A
-  // fragments of a k stage shared by a group of column blocks) once B is well beyond the caches.
-  // Taller A goes to the tile kernels below, which stage A through LDS once per tile: from three
-  // row tiles on they are faster (64 x 28672 x 8192: 92-103 us against 108 us for the 64-column
-  // streaming form and 177 us for the 16-column one; 64 x 14336 x 4096: 20 us against 28 / 43 us).
+  // ---- the tile kernels: workgroup tile and K split
+  // The candidate that needs the least time over the whole grid: (rounds of one workgroup per CU)
+  // x (K steps of 64) x (its measured time per K step: two-group 256x256 kernel 1.17 us, older
+  // 256x256 kernel 1.8 us; small tiles with the K steps split over 2 to 4 groups of wavefronts
+  // inside the workgroup: 128x128 0.575 us, 64x128 0.37 us, 64x64 0.22 us; unsplit, for fewer than
+  // 8 K steps: 0.60, 0.41, 0.35); ties go to the larger tile. (3072^3, 144 big tiles: 1033 TFLOP/s
+  // against 739 with 576 tiles of 128x128; 2048^3, 64 big tiles: 437 against 758; 256 x 4096 x
+  // 4096: 482 with 256 split tiles of 64x64, 326 unsplit, 244 with 64 tiles of 128x128.)
+  // Never less than the time the operands take to arrive: A and B once, at 5.2 TB/s when every CU
+  // has a workgroup pulling (measured: 64 x 8192 x 28672 in 91 us), proportionally less with fewer
+  // workgroups than CUs (the same problem on 128 workgroups: 154 us).
+  // On top of that the K steps may be split over 2, 4 or 8 workgroups per tile (the small-tile
+  // kernels), when the tiles alone leave most of the chip idle against a long K: each part writes
+  // an fp32 partial tile to a scratch and a second kernel adds the parts in a fixed order
+  // (deterministic; no atomics). Its price in the same units: a launch (4 us) plus writing and
+  // reading parts * M * N floats at about 4 TB/s.
+  DeviceInfo di;
+  const int64_t NCU = device_info(di) && di.ncu > 0 ? di.ncu : 256;
+  const int64_t KT = (g.K + 63) / 64;
+  auto cost = [&](int64_t bm, int64_t bn, int64_t t_step, int parts) {
+    const int64_t wgs = ((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * parts;
+    const int64_t rounds = (wgs + NCU - 1) / NCU;
+    const int64_t steps = (KT + parts - 1) / parts;
+    const int64_t compute = rounds * steps * t_step;
+    const int64_t pulling = wgs < NCU ? wgs : NCU;
+    const int64_t arrive = (g.M + g.N) * g.K * 2 * NCU / (5200 * pulling);
+    return (compute > arrive ? compute : arrive) + (parts > 1 ? 4000 + 2 * parts * g.M * g.N / 1000 : 0);
+  };
+  // Among the candidates within 8 % of the best estimate the largest tile wins, then the fewest
+  // parts (a larger tile re-reads its operands from L2 less often, which the estimate leaves out:
+  // 64 x 8192 x 28672 measured 90 us on 64x128 tiles in four parts, 100 us on 64x64 tiles in two).
+  const bool pp = gemm_pp_ok(g);
+  struct Cand { int variant; int bm, bn; int64_t t; };
+  const Cand big = {pp ? GEMM_256_PP16 : GEMM_256_W8, 256, 256, pp ? 1170 : 1800};
+  const Cand split[] = {{GEMM_128_K2, 128, 128, 575}, {GEMM_64X128_K2, 64, 128, 370}, {GEMM_64_K4, 64, 64, 220}};
+  const Cand whole[] = {{GEMM_128_W8, 128, 128, 600}, {GEMM_64X128_W8, 64, 128, 410}, {GEMM_64_W4, 64, 64, 350}};
+  struct Choice { int variant, parts, area; int64_t t; };
+  Choice all[16];
+  int n_all = 0;
+  // no tile taller or wider than the matrix rounded up to 64 (it would multiply padding)
+  auto fits = [&](int bm, int bn) {
+    return !(bm > 64 && bm > (g.M + 63) / 64 * 64) && !(bn > 64 && bn > (g.N + 63) / 64 * 64);
+  };
+  if (g.forced_parts <= 1 && fits(256, 256)) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 1)};
+  for (int parts = g.forced_parts > 0 ? g.forced_parts : 1; parts <= (g.forced_parts > 0 ? g.forced_parts : 8); parts *= 2) {
+    // every part keeps at least 8 K steps, and its partial tiles must fit the scratch allowed
+    if (parts > 1 && KT < 8 * parts) break;
+    if (parts > 1 && g.scratch_limit >= 0 && (int64_t)parts * g.M * g.N * 4 > g.scratch_limit) break;
+    for (const auto& c : KT / parts >= 8 ? split : whole) {
+      if (!fits(c.bm, c.bn)) continue;
+      all[n_all++] = Choice{c.variant, parts, c.bm * c.bn, cost(c.bm, c.bn, c.t, parts)};
+    }
+  }
+  if (n_all == 0) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 1)};
+  int64_t best = all[0].t;
+  for (int i = 1; i < n_all; ++i) best = all[i].t < best ? all[i].t : best;
+  Choice pick = all[0];
+  bool have = false;
+  for (int i = 0; i < n_all; ++i) {
+    if (all[i].t > best + best / 12) continue;
+    if (!have || all[i].area > pick.area || (all[i].area == pick.area && all[i].parts < pick.parts)) pick = all[i];
+    have = true;
+  }
+  int v = pick.variant;
+  const int best_parts = pick.parts;
+  // ---- the skinny kernels (B stored N x K, no LDS staging of A): the automatic choice for one
+  // 16-row tile of A, and for two when they beat the tile kernels' estimate; B streamed through
+  // an LDS ring (16 columns x 512 k per stage, the A fragments of a k stage shared by a group of
+  // column blocks) once B is well beyond the caches: measured 5.4 TB/s of B for M <= 16 and
+  // 3.9 TB/s for two row tiles (32 x 8192 x 28672: 125 us, against 91 us for the tile kernels with
+  // K split four ways). Taller A goes to the tile kernels, which stage A through LDS once per
+  // tile (64 x 28672 x 8192: 92-103 us against 177 us streaming; 64 x 14336 x 4096: 20 us against
+  // 43 us).
   const bool big_b = g.N * g.K >= ((int64_t)1 << 25);
-  const bool skinny_auto = g.forced == GEMM_AUTO && g.M <= 32;
+  const bool stream_wins = g.M <= 16 || g.N * g.K * 2 / 3900 < best;
+  const bool skinny_auto = g.forced == GEMM_AUTO && g.M <= 32 && (!big_b || stream_wins);
   if ((g.forced == GEMM_SKINNY_DMA || (skinny_auto && big_b)) && gemm_skinny_dma_ok(g)) {
     p.variant = GEMM_SKINNY_DMA;
     p.name = "gemm_nt_skinny_16cols_stream";
@@ -517,33 +647,15 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
     return p;
   }
-  // Workgroup tile: the candidate that needs the least time per K step over the whole grid, i.e.
-  // (rounds of 256 workgroups, one per CU) x (its measured time per K step of 64): two-group
-  // 256x256 kernel 1.17 us, older 256x256 kernel 1.8 us; small tiles with the K steps split over
-  // 2 to 4 groups of wavefronts inside the workgroup: 128x128 0.575 us, 64x128 0.37 us, 64x64
-  // 0.22 us (unsplit, for K < 512: 0.60, 0.41, 0.35); ties go to the larger tile. (3072^3, 144
-  // big tiles: 1033 TFLOP/s against 739 with 576 tiles of 128x128; 2048^3, 64 big tiles: 437
-  // against 758; 256 x 4096 x 4096: 482 with 256 split tiles of 64x64, 326 unsplit, 244 with 64
-  // tiles of 128x128.)
-  constexpr int64_t NCU = 256;
-  auto rounds = [&](int64_t bm, int64_t bn) {
-    const int64_t tiles = ((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
-    return (tiles + NCU - 1) / NCU;
-  };
-  const bool pp = gemm_pp_ok(g);
-  int v = pp ? GEMM_256_PP16 : GEMM_256_W8;
-  int64_t best = rounds(256, 256) * (pp ? 1170 : 1800);
-  struct Cand { int variant; int bm, bn; int64_t t; };
-  const Cand split[] = {{GEMM_128_K2, 128, 128, 575}, {GEMM_64X128_K2, 64, 128, 370}, {GEMM_64_K4, 64, 64, 220}};
-  const Cand whole[] = {{GEMM_128_W8, 128, 128, 600}, {GEMM_64X128_W8, 64, 128, 410}, {GEMM_64_W4, 64, 64, 350}};
-  for (const auto& c : g.K >= 512 ? split : whole) {
-    const int64_t cost = rounds(c.bm, c.bn) * c.t;
-    if (cost < best) { best = cost; v = c.variant; }
-  }
   if (g.forced >= GEMM_256 && g.forced < GEMM_NUM_VARIANTS && g.forced != GEMM_SKINNY &&
       g.forced != GEMM_SKINNY_DMA)
     v = g.forced;
   if ((v == GEMM_256_PP16 || v == GEMM_256_W4) && !gemm_pp_ok(g)) v = GEMM_256_W8;
+  // a forced kernel keeps the split only if it is one of the kernels that can run it
+  const bool can_split = v == GEMM_128_K2 || v == GEMM_64X128_K2 || v == GEMM_64_K4 || v == GEMM_128_W8 ||
+                         v == GEMM_64X128_W8 || v == GEMM_64_W4;
+  p.parts = can_split ? best_parts : 1;
+  p.scratch_bytes = p.parts > 1 ? (int64_t)p.parts * g.M * g.N * 4 : 0;
   p.variant = v;
   p.bk = 64;
   switch (v) {
@@ -615,8 +727,63 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
   return MLT_ERR_UNSUPPORTED;
 }
 
-int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
-  return g.dtype == MLT_BF16 ? run_gemm_t<bf16_tag>(g, p, s) : run_gemm_t<f16_tag>(g, p, s);
+// Scratch for the partial products of a K split across workgroups: one buffer per (device, stream)
+// pair, so that calls on different streams never share one; allocated at the first call that needs
+// it (hipMalloc; no device synchronisation), grown by doubling (the smaller buffer is kept until the
+// process ends: work already enqueued may still use it), used in stream order. The table is
+// small and fixed; when it is full, or an allocation fails, the call gets a stream-ordered
+// allocation of its own (or, if that fails too, runs without the split).
+namespace {
+struct ScratchSlot { int dev; hipStream_t stream; float* ptr; int64_t bytes; };
+constexpr int kScratchSlots = 32;
+ScratchSlot g_scratch[kScratchSlots];
+int g_scratch_used = 0;
+std::mutex g_scratch_mu;
+
+float* cached_scratch(int64_t bytes, hipStream_t s) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  ScratchSlot* slot = nullptr;
+  for (int i = 0; i < g_scratch_used; ++i)
+    if (g_scratch[i].dev == dev && g_scratch[i].stream == s) slot = &g_scratch[i];
+  if (slot && slot->bytes >= bytes) return slot->ptr;
+  if (!slot) {
+    if (g_scratch_used == kScratchSlots) return nullptr;
+    slot = &g_scratch[g_scratch_used];
+    *slot = ScratchSlot{dev, s, nullptr, 0};
+  }
+  int64_t want = slot->bytes > 0 ? 2 * slot->bytes : (int64_t)4 << 20;
+  while (want < bytes) want *= 2;
+  void* p = nullptr;
+  if (hipMalloc(&p, (size_t)want) != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
+  if (slot == &g_scratch[g_scratch_used]) ++g_scratch_used;
+  slot->ptr = static_cast<float*>(p);
+  slot->bytes = want;
+  return slot->ptr;
+}
+}  // namespace
+
+int run_gemm(const GemmArgs& g_in, const GemmPlan& p, hipStream_t s) {
+  GemmArgs g = g_in;
+  g.parts = p.parts;
+  bool own = false;
+  if (p.parts > 1 && !g.scratch) {
+    g.scratch = cached_scratch(p.scratch_bytes, s);
+    if (!g.scratch) {
+      void* ws = nullptr;
+      if (hipMallocAsync(&ws, (size_t)p.scratch_bytes, s) == hipSuccess && ws) {
+        g.scratch = static_cast<float*>(ws);
+        own = true;
+      } else {
+        (void)hipGetLastError();
+        g.parts = 1;
+      }
+    }
+  }
+  const int rc = g.dtype == MLT_BF16 ? run_gemm_t<bf16_tag>(g, p, s) : run_gemm_t<f16_tag>(g, p, s);
+  if (own) (void)hipFreeAsync(g.scratch, s);
+  return rc;
 }
 
 }  // namespace mlt

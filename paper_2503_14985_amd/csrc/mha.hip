@@ -18,12 +18,15 @@ MhaPlan plan_mha(const MhaArgs& a) {
   // launches but 2 % slower when it alternates with the GEMM; for D = 64 it does not fit the 128
   // registers that let two workgroups share a CU (-6 %).
   p.mfma_size = a.forced == MHA_PP16 ? 16 : 32;
-  // The persistent form. Measured, unmasked, 2048 items, time per item against the per-item
-  // kernel: D = 128 gains 25 % at 2 key tiles per item, 8 % at 4, 3 % at 8 and loses 1.5 % at 16,
-  // 3 % at 32 and 4 % at 64 (its loop carries the item bookkeeping). D = 64 has no persistent form
-  // (mha_ps_ok). Forcing it applies wherever it can run; elsewhere the default kernel runs.
-  const bool ps_pays = a.Sk <= 8 * PA_BN;
-  p.persistent = mha_ps_ok(a) && (a.forced == MHA_PS || (a.forced == MHA_AUTO && ps_pays));
+  // The persistent form runs only on request. Measured, unmasked, 2048 items, time per item
+  // against the per-item kernel: D = 128 gains 25 % at 2 key tiles per item, 8 % at 4, 3 % at 8
+  // and loses 1.5 % at 16, 3 % at 32 and 4 % at 64 (its loop carries the item bookkeeping). It is
+  // not the automatic choice even for short sequences: it fetches the next item's Q operand with
+  // loads the compiler cannot see into registers the compiler manages, which holds for the
+  // compiler this library is built with (the build's own check of the generated code and the
+  // parity tests say so) but is not a property of the source. D = 64 has no persistent form
+  // (mha_ps_ok). Where the forced form cannot run, the default kernel does.
+  p.persistent = a.forced == MHA_PS && mha_ps_ok(a);
   if (p.persistent) {
     p.mfma_size = 32;
     p.name = "mha_fwd_d128_256x64_ps";

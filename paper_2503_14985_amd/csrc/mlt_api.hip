@@ -1,9 +1,11 @@
 // C ABI of the library: argument validation, variant selection, launch. No device work happens
 // here besides enqueueing kernels on the caller's stream.
 #include <limits.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
+#include "../../include/mlt_diag.h"
 #include "mlt_common.h"
 #include "mlt_internal.h"
 
@@ -13,46 +15,85 @@ namespace {
 
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 thread_local const char* g_last_kernel = "";
+thread_local char g_name_buf[96];
 
-bool device_is_gfx950() {
+// The selected kernel's name; a K split across workgroups shows as a suffix (_splitk2 / 4 / 8).
+void note_gemm_kernel(const GemmPlan& p) {
+  if (p.parts > 1) {
+    snprintf(g_name_buf, sizeof(g_name_buf), "%s_splitk%d", p.name, p.parts);
+    g_last_kernel = g_name_buf;
+  } else {
+    g_last_kernel = p.name;
+  }
+}
+
+struct VariantName { const char* name; int id; };
+const VariantName kGemmVariants[] = {
+    {"general", GEMM_GENERAL}, {"256", GEMM_256}, {"256w8", GEMM_256_W8}, {"256pp16", GEMM_256_PP16},
+    {"256w4", GEMM_256_W4}, {"256w8x1", GEMM_256_W8X1}, {"256w1x8", GEMM_256_W1X8},
+    {"128w8", GEMM_128_W8}, {"64x128", GEMM_64X128_W8}, {"64", GEMM_64_W4}, {"128k2", GEMM_128_K2},
+    {"64x128k2", GEMM_64X128_K2}, {"64k4", GEMM_64_K4}, {"skinny", GEMM_SKINNY},
+    {"skinnydma", GEMM_SKINNY_DMA}};
+const VariantName kMhaVariants[] = {{"pp32", MHA_PP32}, {"pp16", MHA_PP16}, {"ps", MHA_PS}};
+
+// name -> id; "" and "auto" mean the automatic choice; -2 for an unknown name
+template <size_t N>
+int lookup_variant(const VariantName (&table)[N], const char* name, int automatic) {
+  if (!name || !*name || !strcmp(name, "auto")) return automatic;
+  for (const auto& v : table)
+    if (!strcmp(name, v.name)) return v.id;
+  return -2;
+}
+
+Overrides overrides_from_env() {
+  Overrides o;
+  const int g = lookup_variant(kGemmVariants, getenv("MLT_GEMM_VARIANT"), GEMM_AUTO);
+  if (g != -2) o.gemm = g;
+  const int m = lookup_variant(kMhaVariants, getenv("MLT_MHA_VARIANT"), MHA_AUTO);
+  if (m != -2) o.mha = m;
+  if (const char* e = getenv("MLT_MHA_PS_GRID")) {
+    const long v = strtol(e, nullptr, 10);
+    if (v >= 1 && v < (1 << 20)) o.ps_grid = (int)v;
+  }
+  return o;
+}
+
+}  // namespace
+
+namespace mlt {
+
+// The environment is read once, when the first call needs the overrides.
+Overrides& overrides() {
+  static Overrides o = overrides_from_env();
+  return o;
+}
+
+bool device_info(DeviceInfo& out) {
   static thread_local int cached_dev = -1;
-  static thread_local bool cached_ok = false;
+  static thread_local DeviceInfo cached;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return false; }
   if (dev != cached_dev) {
     hipDeviceProp_t p;
     if (hipGetDeviceProperties(&p, dev) != hipSuccess) { (void)hipGetLastError(); return false; }
-    cached_ok = strncmp(p.gcnArchName, "gfx950", 6) == 0;
+    cached.gfx950 = strncmp(p.gcnArchName, "gfx950", 6) == 0;
+    cached.ncu = p.multiProcessorCount;
     cached_dev = dev;
   }
-  return cached_ok;
+  out = cached;
+  return true;
 }
 
-int forced_gemm_variant() {
-  // Tuning/debug override: MLT_GEMM_VARIANT = general | 256 | 128 | 128w8 | 256w8 | 256w8t | 256pp | 256pp16 | 256w4 | skinny | skinnydma | skinnydmaw.
-  const char* e = getenv("MLT_GEMM_VARIANT");
-  if (!e || !*e) return GEMM_AUTO;
-  if (!strcmp(e, "general")) return GEMM_GENERAL;
-  if (!strcmp(e, "256")) return GEMM_256;
-  if (!strcmp(e, "128")) return GEMM_128;
-  if (!strcmp(e, "128w8")) return GEMM_128_W8;
-  if (!strcmp(e, "64x128")) return GEMM_64X128_W8;
-  if (!strcmp(e, "64")) return GEMM_64_W4;
-  if (!strcmp(e, "128k2")) return GEMM_128_K2;
-  if (!strcmp(e, "64x128k2")) return GEMM_64X128_K2;
-  if (!strcmp(e, "64k4")) return GEMM_64_K4;
-  if (!strcmp(e, "256w8")) return GEMM_256_W8;
-  if (!strcmp(e, "256w8t")) return GEMM_256_W8T;
-  if (!strcmp(e, "256pp")) return GEMM_256_PP;
-  if (!strcmp(e, "256w4")) return GEMM_256_W4;
-  if (!strcmp(e, "256pp16")) return GEMM_256_PP16;
-  if (!strcmp(e, "256w8x1")) return GEMM_256_W8X1;
-  if (!strcmp(e, "256w1x8")) return GEMM_256_W1X8;
-  if (!strcmp(e, "skinny")) return GEMM_SKINNY;
-  if (!strcmp(e, "skinnydma")) return GEMM_SKINNY_DMA;
-  if (!strcmp(e, "skinnydmaw")) return GEMM_SKINNY_DMAW;
-  return GEMM_AUTO;
+}  // namespace mlt
+
+namespace {
+
+bool device_is_gfx950() {
+  DeviceInfo d;
+  return device_info(d) && d.gfx950;
 }
+
+int forced_gemm_variant() { return overrides().gemm; }
 
 int check_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
                int64_t ldb, int transB, const void* C, int64_t ldc, int dtype) {
@@ -102,13 +143,14 @@ int mlt_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const 
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
   GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
              (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 0};
+  g.forced_parts = overrides().gemm_parts;
   GemmPlan p = plan_gemm(g);
   hipStream_t s = (hipStream_t)stream;
   {
     TimedRegion t(s);
     rc = run_gemm(g, p, s);
   }
-  if (rc == MLT_OK) g_last_kernel = p.name;
+  if (rc == MLT_OK) note_gemm_kernel(p);
   return rc;
 }
 
@@ -121,13 +163,14 @@ int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, co
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
   GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
              (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 1};
+  g.forced_parts = overrides().gemm_parts;
   GemmPlan p = plan_gemm(g);
   hipStream_t s = (hipStream_t)stream;
   {
     TimedRegion t(s);
     rc = run_gemm(g, p, s);
   }
-  if (rc == MLT_OK) g_last_kernel = p.name;
+  if (rc == MLT_OK) note_gemm_kernel(p);
   return rc;
 }
 
@@ -146,13 +189,14 @@ int mlt_gemm_tiled(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, 
   if (tiling == 1) g.forced = GEMM_256_W8X1;
   if (tiling == 2) g.forced = GEMM_256_W1X8;
   if (tiling == 3) g.forced = gemm_pp_ok(g) ? GEMM_256_W4 : GEMM_256;
+  g.forced_parts = overrides().gemm_parts;
   GemmPlan p = plan_gemm(g);
   hipStream_t s = (hipStream_t)stream;
   {
     TimedRegion t(s);
     rc = run_gemm(g, p, s);
   }
-  if (rc == MLT_OK) g_last_kernel = p.name;
+  if (rc == MLT_OK) note_gemm_kernel(p);
   return rc;
 }
 
@@ -169,13 +213,14 @@ int mlt_gemm_bias_act(int64_t M, int64_t N, int64_t K, const void* A, int64_t ld
              (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 0};
   g.bias = (const uint16_t*)bias;
   g.act = act;
+  g.forced_parts = overrides().gemm_parts;
   GemmPlan p = plan_gemm(g);
   hipStream_t s = (hipStream_t)stream;
   {
     TimedRegion t(s);
     rc = run_gemm(g, p, s);
   }
-  if (rc == MLT_OK) g_last_kernel = p.name;
+  if (rc == MLT_OK) note_gemm_kernel(p);
   return rc;
 }
 
@@ -187,7 +232,7 @@ int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const v
   if (B == 0 || H == 0 || Sq == 0) return MLT_OK;
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
   MhaArgs a{B, H, Sq, Sk, D, (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
-            (uint16_t*)O, scale, causal ? 1 : 0, dtype};
+            (uint16_t*)O, scale, causal ? 1 : 0, dtype, overrides().mha, overrides().ps_grid};
   MhaPlan p = plan_mha(a);
   if (!p.supported) return MLT_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
@@ -232,12 +277,9 @@ static int probe_mfma_impl(int mfma_size, int iters, const void* data, void* sin
                            void* stream) {
   if (iters < 1 || iters > (1 << 20) || !data || !sink || !flop) return MLT_ERR_INVALID_ARG;
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
-  int dev = 0, ncu = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
-    (void)hipGetLastError();
-    return MLT_ERR_DEVICE;
-  }
+  DeviceInfo di;
+  if (!device_info(di)) return MLT_ERR_DEVICE;
+  const int ncu = di.ncu;
   hipStream_t s = (hipStream_t)stream;
   double f;
   {
@@ -263,12 +305,9 @@ int mlt_probe_hbm_read(const void* data, int64_t bytes, void* sink, void* stream
       (reinterpret_cast<uintptr_t>(data) & 15) != 0)
     return MLT_ERR_INVALID_ARG;
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
-  int dev = 0, ncu = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
-    (void)hipGetLastError();
-    return MLT_ERR_DEVICE;
-  }
+  DeviceInfo di;
+  if (!device_info(di)) return MLT_ERR_DEVICE;
+  const int ncu = di.ncu;
   hipStream_t s = (hipStream_t)stream;
   int rc;
   {
@@ -286,6 +325,33 @@ void mlt_set_timing_events(void* start_event, void* stop_event) {
 
 const char* mlt_last_kernel(void) { return g_last_kernel; }
 
+int mlt_diag_force_variant(const char* gemm_variant, const char* mha_variant) {
+  int g = overrides().gemm, m = overrides().mha;
+  if (gemm_variant) {
+    g = lookup_variant(kGemmVariants, gemm_variant, GEMM_AUTO);
+    if (g == -2) return MLT_ERR_INVALID_ARG;
+  }
+  if (mha_variant) {
+    m = lookup_variant(kMhaVariants, mha_variant, MHA_AUTO);
+    if (m == -2) return MLT_ERR_INVALID_ARG;
+  }
+  overrides().gemm = g;
+  overrides().mha = m;
+  return MLT_OK;
+}
+
+int mlt_diag_force_k_parts(int parts) {
+  if (parts != 0 && parts != 1 && parts != 2 && parts != 4 && parts != 8) return MLT_ERR_INVALID_ARG;
+  overrides().gemm_parts = parts;
+  return MLT_OK;
+}
+
+int mlt_diag_set_persistent_grid(int workgroups) {
+  if (workgroups < 0 || workgroups >= (1 << 20)) return MLT_ERR_INVALID_ARG;
+  overrides().ps_grid = workgroups;
+  return MLT_OK;
+}
+
 int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]) {
   if (!dims || !out) return MLT_ERR_INVALID_ARG;
   if (dtype != MLT_BF16 && dtype != MLT_FP16) return MLT_ERR_INVALID_ARG;
@@ -294,7 +360,8 @@ int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]) 
     // Alignment is unknown here: assume aligned pointers and tight leading dimensions.
     GemmArgs g{dims[0], dims[1], dims[2], nullptr, dims[2], nullptr, dims[3] ? dims[2] : dims[1],
                dims[3] ? 1 : 0, nullptr, dims[1], dtype, forced_gemm_variant(), 0};
-    GemmPlan p = plan_gemm(g);
+    g.forced_parts = overrides().gemm_parts;
+  GemmPlan p = plan_gemm(g);
     if (p.variant == GEMM_ZERO) { for (int i = 0; i < 10; ++i) out[i] = 0; return MLT_OK; }
     out[0] = p.bm; out[1] = p.bn; out[2] = p.wm; out[3] = p.wn;
     out[4] = p.bm / p.wm; out[5] = p.bn / p.wn; out[6] = p.mfma_m; out[7] = p.mfma_n;
@@ -305,11 +372,12 @@ int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]) 
     if (dims[0] < 0 || dims[1] < 1) return MLT_ERR_INVALID_ARG;
     if (dims[2] != 64 && dims[2] != 128) return MLT_ERR_UNSUPPORTED;
     MhaArgs a{1, 1, dims[0], dims[1], dims[2], nullptr, nullptr, nullptr, nullptr, 1.f,
-              dims[3] ? 1 : 0, dtype};
+              dims[3] ? 1 : 0, dtype, overrides().mha, overrides().ps_grid};
     MhaPlan p = plan_mha(a);
     if (!p.supported) return MLT_ERR_UNSUPPORTED;
     out[0] = p.bm; out[1] = (int32_t)dims[2]; out[2] = p.waves; out[3] = 1;
-    out[4] = p.bm / p.waves; out[5] = (int32_t)dims[2]; out[6] = 32; out[7] = 32; out[8] = 16;
+    out[4] = p.bm / p.waves; out[5] = (int32_t)dims[2];
+    out[6] = p.mfma_size; out[7] = p.mfma_size; out[8] = p.mfma_size == 16 ? 32 : 16;
     out[9] = p.bn;
     return MLT_OK;
   }

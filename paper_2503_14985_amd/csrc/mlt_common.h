@@ -87,8 +87,10 @@ __device__ __forceinline__ void store_c(uint16_t* C, int64_t idx, float v, int a
 }
 
 // Epilogue word of the GEMM kernels: bit 0 = add into an fp32 C (no bias, no activation);
-// otherwise bits 1..2 = activation applied to acc + bias[col] before rounding to the 16-bit C.
-enum { EPI_ACC32 = 1, EPI_ACT_SHIFT = 1, ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
+// bit 3 = store the fp32 accumulator as it is (a partial product of a K split across workgroups:
+// C then points at this part's slice of the fp32 scratch); otherwise bits 1..2 = activation
+// applied to acc + bias[col] before rounding to the 16-bit C.
+enum { EPI_ACC32 = 1, EPI_ACT_SHIFT = 1, EPI_ACT_MASK = 3, EPI_PART32 = 8, ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
 __device__ __forceinline__ float epi_act(float v, int act) {
   if (act == ACT_RELU) return v > 0.f ? v : 0.f;
   if (act == ACT_GELU) return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));   // v * Phi(v)
@@ -98,12 +100,14 @@ __device__ __forceinline__ float epi_act(float v, int act) {
 // for every element this lane owns that lies inside the matrix.
 template <typename Tag, typename Each>
 __device__ __forceinline__ void gemm_epilogue(Each&& each, uint16_t* C, int epi, const uint16_t* bias) {
-  if (epi & EPI_ACC32) {
+  if (epi & EPI_PART32) {
+    each([&](int64_t idx, int, float v) { reinterpret_cast<float*>(C)[idx] = v; });
+  } else if (epi & EPI_ACC32) {
     each([&](int64_t idx, int, float v) { reinterpret_cast<float*>(C)[idx] += v; });
   } else if (epi == 0 && bias == nullptr) {
     each([&](int64_t idx, int, float v) { C[idx] = Elem<Tag>::from_f32(v); });
   } else {
-    const int act = epi >> EPI_ACT_SHIFT;
+    const int act = (epi >> EPI_ACT_SHIFT) & EPI_ACT_MASK;
     each([&](int64_t idx, int col, float v) {
       if (bias) v += Elem<Tag>::to_f32(bias[col]);
       C[idx] = Elem<Tag>::from_f32(epi_act(v, act));

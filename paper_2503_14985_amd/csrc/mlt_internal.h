@@ -35,12 +35,20 @@ struct GemmArgs {
   int acc32;   // 0: C is 16-bit and overwritten; 1: C is fp32 and accumulated into (C += A*B)
   const uint16_t* bias = nullptr;  // N elements of the input type added to every row (16-bit C only), or null
   int act = 0;                     // 0 none, 1 relu, 2 gelu: applied after the bias (16-bit C only)
+  // K split across workgroups: the fp32 scratch the partial products go to (parts * M * N floats)
+  // and the number of parts the plan asks for; run_gemm fills both in.
+  float* scratch = nullptr;
+  int parts = 1;
+  int64_t scratch_limit = -1;      // plan_gemm: largest scratch (bytes) a split may use; -1 = no limit
+  int forced_parts = 0;            // plan_gemm: 0 = the cost model's choice, 1 / 2 / 4 / 8 = forced
   int epi() const { return acc32 ? 1 : (act << 1); }   // the kernels' epilogue word
   bool fused() const { return bias != nullptr || act != 0; }
 };
 
 struct GemmPlan {
   int variant = GEMM_GENERAL;
+  int parts = 1;                   // > 1: K split across workgroups, partial products through a scratch
+  int64_t scratch_bytes = 0;       // parts * M * N * 4 when parts > 1
   const char* name = "";
   int bm = 0, bn = 0, bk = 0, wm = 0, wn = 0;
   int mfma_m = 32, mfma_n = 32, mfma_k = 16;
@@ -89,7 +97,7 @@ int run_mha_ps(const MhaArgs& a, hipStream_t s);
 // Process-wide overrides of the automatic kernel choice, for tuning and for the tests that must
 // reach every kernel (mlt_diag_force_variant; initial values from MLT_GEMM_VARIANT /
 // MLT_MHA_VARIANT / MLT_MHA_PS_GRID, read once).
-struct Overrides { int gemm = GEMM_AUTO; int mha = MHA_AUTO; int ps_grid = 0; };
+struct Overrides { int gemm = GEMM_AUTO; int gemm_parts = 0; int mha = MHA_AUTO; int ps_grid = 0; };
 Overrides& overrides();
 // Device facts the launchers need, cached per thread for the current device.
 struct DeviceInfo { int ncu = 0; bool gfx950 = false; };

@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "mlt.h")
+DIAG_HEADER = os.path.join(ROOT, "include", "mlt_diag.h")
 
 
 @pytest.fixture(scope="module")
@@ -16,19 +17,46 @@ def binding():
     return b
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(header):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(mlt_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(binding):
-    names = declared_functions()
+    names = declared_functions(HEADER)
     assert {"mlt_gemm", "mlt_mha_fwd", "mlt_status_string", "mlt_version"} <= set(names)
+    diag = declared_functions(DIAG_HEADER)
+    # the operations' header carries no diagnostics
+    assert not [n for n in names if "probe" in n or "diag" in n or "timing" in n or "query" in n]
     lib = binding.raw()
-    for n in names:
+    for n in names + diag:
         assert hasattr(lib, n), "libmlt.so does not export %s" % n
     assert sorted(binding.EXPORTS) == names
+    assert sorted(binding.DIAG_EXPORTS) == diag
+
+
+def test_kernel_choice_overrides(binding):
+    """mlt_diag_force_variant: host-side state only; unknown names are rejected and change nothing;
+    the tiling query reports the MFMA shape of the attention variant in force."""
+    try:
+        binding.mlt_diag_force_variant(mha="pp16")
+        assert binding.mlt_query_tiling(1, (4096, 4096, 128, 0), 0)[6:9] == [16, 16, 32]
+        with pytest.raises(binding.MltError):
+            binding.mlt_diag_force_variant(mha="no-such-kernel")
+        assert binding.mlt_query_tiling(1, (4096, 4096, 128, 0), 0)[6:9] == [16, 16, 32]
+        binding.mlt_diag_force_variant(mha="auto")
+        assert binding.mlt_query_tiling(1, (4096, 4096, 128, 0), 0)[6:9] == [32, 32, 16]
+        binding.mlt_diag_force_variant(gemm="64k4")
+        assert binding.mlt_query_tiling(0, (8192, 8192, 8192, 0), 0)[0:2] == [64, 64]
+        with pytest.raises(binding.MltError):
+            binding.mlt_diag_force_variant(gemm="256pp")        # retired name
+        with pytest.raises(binding.MltError):
+            binding.mlt_diag_set_persistent_grid(-1)
+    finally:
+        binding.mlt_diag_force_variant(gemm="auto", mha="auto")
+        binding.mlt_diag_set_persistent_grid(0)
+    assert binding.mlt_query_tiling(0, (8192, 8192, 8192, 0), 0)[0:2] == [256, 256]
 
 
 def test_status_strings_and_version(binding):

@@ -14,17 +14,19 @@ BF16, FP16 = inputs.BF16, inputs.FP16
 
 @pytest.fixture(autouse=True)
 def _announce(request):
+    from paper_2503_14985_amd import binding
     print("\n[case] %s" % request.node.name, flush=True)
-    os.environ.pop("MLT_GEMM_VARIANT", None)
+    binding.mlt_diag_force_variant(gemm="auto")
+    binding.mlt_diag_force_k_parts(0)
     yield
-    os.environ.pop("MLT_GEMM_VARIANT", None)
+    binding.mlt_diag_force_variant(gemm="auto")
+    binding.mlt_diag_force_k_parts(0)
 
 
 def _go(M, N, K, dtype, transB, dist="normal", std=1.0, seed=0, variant=None, **pads):
     from paper_2503_14985_amd import binding
     A, B = inputs.gemm_inputs(M, N, K, dtype, seed, dist=dist, std=std, transB=transB)
-    if variant:
-        os.environ["MLT_GEMM_VARIANT"] = variant
+    binding.mlt_diag_force_variant(gemm=variant or "auto")
     C = pu.run_gemm(A, B, dtype, transB=transB, lda=pads.get("lda"), ldb=pads.get("ldb"),
                     ldc_pad=pads.get("ldc_pad", 0))
     st = pu.check_gemm(A, B, C, dtype, transB, seed=seed)
@@ -37,7 +39,7 @@ def test_config1_bf16_512_uniform():
     assert name.startswith("gemm_nn")
 
 
-@pytest.mark.parametrize("variant", ["256", "128", "128w8", "64x128", "64", "128k2", "64x128k2", "64k4", "general"])
+@pytest.mark.parametrize("variant", ["256", "256w8", "128w8", "64x128", "64", "128k2", "64x128k2", "64k4", "general"])
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 def test_small_multi_tile_ragged(variant, transB, dtype):
@@ -45,7 +47,7 @@ def test_small_multi_tile_ragged(variant, transB, dtype):
     _go(520, 776, 328, dtype, transB, variant=variant, seed=1)
 
 
-@pytest.mark.parametrize("variant", ["256", "128", "128w8"])
+@pytest.mark.parametrize("variant", ["256", "256w8", "128w8"])
 @pytest.mark.parametrize("transB", [False, True])
 def test_exact_tiles(variant, transB):
     _go(512, 768, 256, BF16, transB, variant=variant, seed=2)
@@ -54,13 +56,12 @@ def test_exact_tiles(variant, transB):
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("shape", [(520, 776, 320), (512, 768, 256), (100, 40, 64), (257, 264, 128)])
-@pytest.mark.parametrize("form", ["256pp", "256pp16"])
-def test_two_group_kernel(shape, transB, dtype, form):
-    # the direct-to-LDS two-group kernel in both MFMA shapes (32x32x16, 16x16x32): K a multiple of
-    # 64, ragged and exact M/N, one and many K steps
+def test_two_group_kernel(shape, transB, dtype):
+    # the direct-to-LDS two-group kernel (16x16x32 MFMAs): K a multiple of 64, ragged and exact
+    # M/N, one and many K steps
     M, N, K = shape
-    name, _ = _go(M, N, K, dtype, transB, variant=form, seed=6)
-    assert name.endswith("_pp16" if form == "256pp16" else "_pp")
+    name, _ = _go(M, N, K, dtype, transB, variant="256pp16", seed=6)
+    assert name.endswith("_pp16")
 
 
 @pytest.mark.parametrize("dtype", [BF16, FP16])
@@ -97,7 +98,7 @@ def test_skinny_kernel(shape, dtype):
     assert "skinny" in name
     # the same problem through the tile kernel must agree with the oracle too (and is what a
     # row-major B or a larger M gets)
-    name, _ = _go(M, N, K, dtype, True, std=0.02, seed=7, variant="128")
+    name, _ = _go(M, N, K, dtype, True, std=0.02, seed=7, variant="128w8")
     assert "skinny" not in name
 
 
@@ -105,10 +106,9 @@ def test_skinny_kernel(shape, dtype):
 @pytest.mark.parametrize("shape", [(16, 1024, 512), (1, 1031, 520), (17, 2048, 4096 + 8), (64, 1040, 1024),
                                    (33, 4096, 8), (48, 1500, 7000), (16, 16 * 300 + 5, 1536),
                                    (20, 64 * 300 + 21, 1160), (16, 40965, 520), (8, 36880, 1536)])
-@pytest.mark.parametrize("form", ["skinnydma", "skinnydmaw"])
-def test_skinny_streaming_kernel(shape, dtype, form):
-    # B streamed through the LDS ring by persistent workgroups, in both stage shapes (16 columns x
-    # 512 k, 64 columns x 128 k): one to four 16-row tiles of A, ragged N (clamped rows), K below /
+def test_skinny_streaming_kernel(shape, dtype, form="skinnydma"):
+    # B streamed through the LDS ring by persistent workgroups (stages of 16 columns x 512 k): one
+    # to four 16-row tiles of A, ragged N (clamped rows), K below /
     # equal to / not a multiple of the stage, a single 8-wide K, and more column blocks than CUs
     # (several blocks per workgroup, the ring wrapping across block ends; the last two shapes give
     # a workgroup more blocks than one group holds: full and partial groups, odd and even numbers
@@ -118,21 +118,93 @@ def test_skinny_streaming_kernel(shape, dtype, form):
     assert name.endswith("cols_stream")
 
 
+@pytest.mark.parametrize("parts", [2, 4, 8])
+@pytest.mark.parametrize("variant", ["64k4", "64x128k2", "128k2", "128w8", "64"])
+@pytest.mark.parametrize("transB", [False, True])
+def test_k_split_across_workgroups(variant, transB, parts):
+    """The K steps of a tile split over 2, 4 or 8 workgroups (Section 4.1's memory-bound shapes: few
+    tiles against a long K): fp32 partial tiles through the scratch, added in a fixed order by the
+    second kernel, which also applies the epilogue. Ragged M and N, K not a multiple of the step
+    (the last part is shorter, its last step partial), parts that do not divide the steps."""
+    from paper_2503_14985_amd import binding
+    binding.mlt_diag_force_k_parts(parts)
+    for dtype, (M, N, K) in ((BF16, (200, 328, 64 * 67 + 8)), (FP16, (70, 136, 64 * 70))):
+        name, _ = _go(M, N, K, dtype, transB, variant=variant, seed=50 + parts)
+        assert name.endswith("_splitk%d" % parts), name
+    # too few K steps for that many parts: the split is dropped, not the kernel
+    name, _ = _go(100, 72, 64 * 4, BF16, transB, variant=variant, seed=51)
+    assert "splitk" not in name
+
+
+def test_k_split_results_do_not_depend_on_the_run():
+    """Fixed-order reduction: the same call twice gives the same bits (no atomics), and the split
+    result meets the oracle bound like the unsplit one."""
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    A, B = inputs.gemm_inputs(64, 1024, 64 * 96, BF16, 60, transB=True, std=0.02)
+    tA, tB = inputs.bits_to_torch(A, BF16, dev), inputs.bits_to_torch(B, BF16, dev)
+    binding.mlt_diag_force_k_parts(4)
+    c1 = binding.mlt_gemm(tA, tB, transB=True).clone()
+    c2 = binding.mlt_gemm(tA, tB, transB=True)
+    torch.cuda.synchronize()
+    assert "splitk4" in binding.mlt_last_kernel()
+    assert torch.equal(c1.view(torch.int16), c2.view(torch.int16))
+    pu.check_gemm(A, B, c2, BF16, True, seed=60)
+
+
+@pytest.mark.parametrize("parts", [2, 8])
+def test_k_split_with_fp32_accumulate_and_fused_epilogue(parts):
+    """The split's second kernel carries the epilogue: C(fp32) += A*B and act(A*B + bias)."""
+    import oracle
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    binding.mlt_diag_force_k_parts(parts)
+    binding.mlt_diag_force_variant(gemm="64k4")
+    M, N, K = 130, 200, 64 * 70
+    A, B = inputs.gemm_inputs(M, N, K, BF16, 61, transB=True)
+    C0 = np.random.default_rng(61).standard_normal((M, N)).astype(np.float32) * 10.0
+    Ct = torch.from_numpy(C0.copy()).to(dev)
+    binding.mlt_gemm_acc(inputs.bits_to_torch(A, BF16, dev), inputs.bits_to_torch(B, BF16, dev), Ct, transB=True)
+    torch.cuda.synchronize()
+    assert binding.mlt_last_kernel().endswith("_splitk%d" % parts)
+    Cref, T = oracle.gemm(A, B, BF16, transB=True)
+    err = np.abs(Ct.double().cpu().numpy() - (C0.astype(np.float64) + Cref))
+    bound = (K * 2.0 ** -24) * T + 2.0 ** -22 * (np.abs(C0) + T) + 1e-6
+    assert np.all(err <= bound), "worst err/bound %.3f" % float(np.max(err / bound))
+    bias = inputs.bias_input(N, BF16, 61, std=4.0)
+    st = pu.run_check_gemm_bias_act(A, B, bias, 2, BF16, transB=True)
+    assert binding.mlt_last_kernel().endswith("_splitk%d" % parts)
+    print("   %s" % st, flush=True)
+
+
+@pytest.mark.parametrize("shape", [(64, 8192, 28672), (512, 4096, 14336), (48, 8192, 28672 + 8)])
+def test_k_split_is_chosen_for_few_tiles_against_a_long_k(shape):
+    """Full-size memory-bound shapes in the launch configuration the library picks by itself."""
+    M, N, K = shape
+    name, _ = _go(M, N, K, BF16, True, std=0.02, seed=0)
+    assert "splitk" in name, name
+
+
 def test_skinny_routing():
-    # one or two 16-row tiles of A and B of 2^25 elements: the streaming kernel without any override
+    # one 16-row tile of A and B of 2^25 elements: the streaming kernel without any override
     name, _ = _go(16, 8192, 4096, BF16, True, std=0.02, seed=9)
-    assert name.endswith("16cols_stream")
-    name, _ = _go(17, 8192, 4096, BF16, True, std=0.02, seed=9)
     assert name.endswith("16cols_stream")
     name, _ = _go(16, 4096, 4096, BF16, True, std=0.02, seed=9)       # smaller B: K split over the wavefronts
     assert name.endswith("skinny_16cols_ksplit8")
     name, _ = _go(30, 4096, 2048, BF16, True, std=0.02, seed=9)
     assert name.endswith("skinny_16cols_ksplit8")
+    # two row tiles against a large B: whichever of the streaming kernel and the tile kernels the
+    # estimate favours (a long K with few columns goes to the tile kernels with K split across
+    # workgroups, many columns stay with the streaming kernel or unsplit tiles)
+    name, _ = _go(17, 8192, 4096, BF16, True, std=0.02, seed=9)
+    assert "16cols_stream" in name or "_k" in name
+    name, _ = _go(32, 4096, 28672, BF16, True, std=0.02, seed=9)
+    assert "splitk" in name
     # taller A: the tile kernels (small tiles, K split inside the workgroup)
     name, _ = _go(40, 16384, 2048, FP16, True, std=0.02, seed=9)
     assert "skinny" not in name and "_k" in name
     name, _ = _go(64, 4096, 4096, BF16, True, std=0.02, seed=9)
-    assert name.endswith("64x64x64_w2x2_k4")
+    assert "64x64x64_w2x2_k4" in name
 
 
 @pytest.mark.parametrize("variant", ["128k2", "64x128k2", "64k4"])
@@ -178,16 +250,17 @@ def test_padded_leading_dimensions(transB):
     # an even ldc keeps the paired 32-bit stores of the tile kernels: odd M, padding must stay untouched
     for variant in ("128w8", "64k4", "256"):
         _go(301, N, K, FP16, transB, seed=4, lda=K + 8, ldb=(K if transB else N) + 16, ldc_pad=6, variant=variant)
-    os.environ.pop("MLT_GEMM_VARIANT", None)
+    from paper_2503_14985_amd import binding
+    binding.mlt_diag_force_variant(gemm="auto")
     # unaligned leading dimensions must fall back to the general kernel and still be right
     name, _ = _go(70, N, K, BF16, transB, seed=4, lda=K + 3, ldb=(K if transB else N) + 1, ldc_pad=1)
     assert "general" in name
 
 
 @pytest.mark.parametrize("variant,shape,transB", [("256pp16", (300, 264, 192), False), ("256pp16", (300, 264, 192), True),
-                                                  ("256pp", (300, 264, 192), False), ("256w4", (300, 264, 192), False),
+                                                  ("256w4", (300, 264, 192), False),
                                                   ("256w4", (300, 264, 192), True), ("skinnydma", (16, 1100, 1032), True),
-                                                  ("skinnydmaw", (40, 1100, 1032), True), ("skinny", (16, 1100, 1032), True)])
+                                                  ("skinnydma", (40, 1100, 1032), True), ("skinny", (16, 1100, 1032), True)])
 def test_padded_leading_dimensions_direct_load_kernels(variant, shape, transB):
     # row strides larger than the rows (NaN-filled padding that must never be read into a result
     # or written) through the kernels that address global memory with per-lane byte offsets
@@ -250,17 +323,17 @@ def test_config3_llm_shapes_transB(shape):
 
 
 @pytest.mark.parametrize("shape,suffix", [((16, 28672, 8192), "16cols_stream"), ((1, 28672, 8192), "16cols_stream"),
-                                          ((64, 28672, 4096), "64x128x64_w2x4_k2"), ((16, 131072, 4096), "16cols_stream"),
-                                          ((32, 8192, 28672), "16cols_stream"), ((64, 8192, 28672), "64x64x64_w2x2_k4")])
+                                          ((64, 28672, 4096), "_k"), ((16, 131072, 4096), "16cols_stream"),
+                                          ((32, 8192, 28672), "_splitk4"), ((64, 8192, 28672), "_splitk4")])
 def test_decode_shapes_streaming_kernels_full_size(shape, suffix):
     # the memory-bound decode GEMMs at their real sizes, in the launch configuration the library
     # picks (persistent workgroups, several column blocks each); sampled against the oracle
     M, N, K = shape
     name, _ = _go(M, N, K, BF16, True, std=0.02, seed=0)
-    assert name.endswith(suffix)
+    assert suffix in name
 
 
-@pytest.mark.parametrize("variant", [None, "256pp", "128", "general"])
+@pytest.mark.parametrize("variant", [None, "256pp16", "128w8", "general"])
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 def test_accumulate_into_fp32_c(variant, transB, dtype):
@@ -275,8 +348,7 @@ def test_accumulate_into_fp32_c(variant, transB, dtype):
     C0 = rng.standard_normal((M, N)).astype(np.float32) * 10.0
     dev = torch.device("cuda:0")
     Ct = torch.from_numpy(C0.copy()).to(dev)
-    if variant:
-        os.environ["MLT_GEMM_VARIANT"] = variant
+    binding.mlt_diag_force_variant(gemm=variant or "auto")
     At, Bt = inputs.bits_to_torch(A, dtype, dev), inputs.bits_to_torch(B, dtype, dev)
     binding.mlt_gemm_acc(At, Bt, Ct, transB=transB)
     binding.mlt_gemm_acc(At, Bt, Ct, transB=transB)          # twice: C0 + 2 A*B
@@ -310,8 +382,8 @@ def test_accumulate_edge_cases():
 
 @pytest.mark.parametrize("act", [0, 1, 2])
 @pytest.mark.parametrize("with_bias", [False, True])
-@pytest.mark.parametrize("variant,shape", [("256pp", (520, 776, 320)), ("256", (300, 264, 200)),
-                                           ("128", (260, 392, 136)), ("general", (70, 53, 29)),
+@pytest.mark.parametrize("variant,shape", [("256pp16", (520, 776, 320)), ("256", (300, 264, 200)),
+                                           ("128w8", (260, 392, 136)), ("general", (70, 53, 29)),
                                            (None, (16, 2048, 512))])
 def test_fused_bias_activation(variant, shape, with_bias, act):
     """C = act(A*B + bias) through every kernel family's epilogue (several tiles, ragged edges);
@@ -321,15 +393,14 @@ def test_fused_bias_activation(variant, shape, with_bias, act):
     for dtype, transB in ((BF16, False), (FP16, True)):
         A, B = inputs.gemm_inputs(M, N, K, dtype, 11, transB=transB)
         bias = inputs.bias_input(N, dtype, 11, std=4.0) if with_bias else None
-        if variant:
-            os.environ["MLT_GEMM_VARIANT"] = variant
+        binding.mlt_diag_force_variant(gemm=variant or "auto")
         st = pu.run_check_gemm_bias_act(A, B, bias, act, dtype, transB=transB)
         name = binding.mlt_last_kernel()
         print("   kernel=%s %s" % (name, st), flush=True)
         if with_bias or act:
             assert "skinny" not in name
-        if variant == "256pp":
-            assert name.endswith("_pp")
+        if variant == "256pp16":
+            assert name.endswith("_pp16")
 
 
 def test_fused_epilogue_edge_cases():

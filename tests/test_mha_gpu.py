@@ -16,12 +16,13 @@ BF16, FP16 = inputs.BF16, inputs.FP16
 
 @pytest.fixture(autouse=True)
 def _announce(request):
+    from paper_2503_14985_amd import binding
     print("\n[case] %s" % request.node.name, flush=True)
-    os.environ.pop("MLT_MHA_VARIANT", None)
-    os.environ.pop("MLT_MHA_PS_GRID", None)
+    binding.mlt_diag_force_variant(mha="auto")
+    binding.mlt_diag_set_persistent_grid(0)
     yield
-    os.environ.pop("MLT_MHA_VARIANT", None)
-    os.environ.pop("MLT_MHA_PS_GRID", None)
+    binding.mlt_diag_force_variant(mha="auto")
+    binding.mlt_diag_set_persistent_grid(0)
 
 
 def _go(B, H, Sq, Sk, D, dtype, causal, seed=0, scale=None, q_gain=1.0, **kw):
@@ -54,7 +55,7 @@ def test_every_kernel_variant(variant, causal, D, dtype):
     # the persistent form exists for unmasked D = 128 only; elsewhere the request falls back to the
     # default kernel
     suffix = {"pp16": "_pp16", "pp32": "_pp", "ps": "_ps" if (D == 128 and not causal) else "_pp"}[variant]
-    os.environ["MLT_MHA_VARIANT"] = variant
+    binding.mlt_diag_force_variant(mha=variant)
     _go(1, 2, 600, 455, D, dtype, causal, seed=11)
     assert binding.mlt_last_kernel().endswith(suffix)
     _go(2, 1, 300, 300, D, dtype, causal, seed=12, q_gain=3.0, rounding_aware=True)
@@ -97,9 +98,8 @@ def test_persistent_kernel_walks_items(grid, dtype, D=128):
     (the last query tile of (3, 5, 300, .) leaves wavefronts without any row), a negative scale,
     peaky rows."""
     from paper_2503_14985_amd import binding
-    os.environ["MLT_MHA_VARIANT"] = "ps"
-    if grid:
-        os.environ["MLT_MHA_PS_GRID"] = str(grid)
+    binding.mlt_diag_force_variant(mha="ps")
+    binding.mlt_diag_set_persistent_grid(grid)
     for (B, H, Sq, Sk, kw) in [(3, 5, 300, 200, {}), (1, 7, 700, 128, {}), (2, 3, 512, 435, {"q_gain": 3.0}),
                                (1, 9, 256, 100, {"scale": -0.11}), (1, 2, 1100, 65, {})]:
         _go(B, H, Sq, Sk, D, dtype, False, seed=31 + Sk, **kw)
@@ -112,11 +112,9 @@ def test_persistent_kernel_walks_items(grid, dtype, D=128):
     # D = 64 has no persistent form, forced or not
     _go(1, 2, 300, 200, 64, dtype, False, seed=9)
     assert binding.mlt_last_kernel().endswith("_pp")
-    # default routing: D = 128 with at most 8 key tiles per item
-    os.environ.pop("MLT_MHA_VARIANT", None)
+    # the automatic choice never takes the persistent form
+    binding.mlt_diag_force_variant(mha="auto")
     _go(1, 2, 300, 200, D, dtype, False, seed=7)
-    assert binding.mlt_last_kernel().endswith("_ps")
-    _go(1, 1, 256, 1100, D, dtype, False, seed=8)
     assert binding.mlt_last_kernel().endswith("_pp")
 
 

@@ -18,8 +18,9 @@ BF16, FP16 = inputs.BF16, inputs.FP16
 @pytest.fixture(autouse=True)
 def _announce(request):
     print("\n[case] %s" % request.node.name, flush=True)
-    for v in ("MLT_GEMM_VARIANT", "MLT_MHA_VARIANT", "MLT_MHA_PS_GRID"):
-        os.environ.pop(v, None)
+    from paper_2503_14985_amd import binding
+    binding.mlt_diag_force_variant(gemm="auto", mha="auto")
+    binding.mlt_diag_set_persistent_grid(0)
     yield
 
 
