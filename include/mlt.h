@@ -34,7 +34,8 @@ typedef enum {
   MLT_ERR_INVALID_ARG = -1, /* null pointer, negative size, leading dimension too small, bad dtype */
   MLT_ERR_UNSUPPORTED = -2, /* valid request with no kernel (e.g. head dimension not 64 or 128) */
   MLT_ERR_LAUNCH = -3,      /* the HIP runtime rejected the kernel launch */
-  MLT_ERR_DEVICE = -4       /* no usable gfx950 device is current */
+  MLT_ERR_DEVICE = -4,      /* no usable gfx950 device is current */
+  MLT_ERR_SCRATCH = -5      /* mlt_gemm_noalloc: the call needs more than the fixed scratch array holds */
 } mlt_status;
 
 /*
@@ -55,6 +56,22 @@ typedef enum {
  */
 int mlt_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
              int64_t ldb, int transB, void* C, int64_t ldc, int dtype, void* stream);
+
+/*
+ * mlt_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc. Same arguments, same kernels and the same
+ * result, bit for bit, as mlt_gemm. Where mlt_gemm splits K across workgroups (few tiles against
+ * a long K) and keeps the fp32 partial products in a scratch buffer it allocates, this entry point
+ * keeps them in a fixed array of 32 MiB in device memory that is part of the library (one copy
+ * per GPU the library runs on, held until the process ends). It calls no hipMalloc, hipFree or
+ * other allocating routine. The library's own choice of a split never needs more than 16 MiB;
+ * a split forced through mlt_diag_force_k_parts that needs more than 32 MiB (parts * M * N * 4
+ * bytes) is refused with MLT_ERR_SCRATCH and nothing is enqueued. All calls on one GPU share that
+ * GPU's array: two calls of this entry point that may run at the same time on one GPU (different
+ * streams) race; calls on one stream, and calls on different GPUs, do not.
+ */
+int mlt_gemm_noalloc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                     int64_t ldb, int transB, void* C, int64_t ldc, int dtype, void* stream);
 
 /*
  * The paper's own form of the GEMM (Section 2, Listing 1): C += A * B with C in fp32, i.e. the

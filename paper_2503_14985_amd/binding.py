@@ -17,9 +17,10 @@ LIB_PATH = os.path.join(_HERE, "libmlt.so")
 
 MLT_BF16, MLT_FP16 = 0, 1
 MLT_OK, MLT_ERR_INVALID_ARG, MLT_ERR_UNSUPPORTED, MLT_ERR_LAUNCH, MLT_ERR_DEVICE = 0, -1, -2, -3, -4
+MLT_ERR_SCRATCH = -5
 
 # include/mlt.h (the operations) and include/mlt_diag.h (probes, timing hooks, kernel-choice overrides)
-EXPORTS = ("mlt_gemm", "mlt_gemm_acc", "mlt_gemm_tiled", "mlt_gemm_bias_act", "mlt_mha_fwd",
+EXPORTS = ("mlt_gemm", "mlt_gemm_noalloc", "mlt_gemm_acc", "mlt_gemm_tiled", "mlt_gemm_bias_act", "mlt_mha_fwd",
            "mlt_paged_attn_decode", "mlt_status_string", "mlt_version")
 DIAG_EXPORTS = ("mlt_probe_mfma", "mlt_probe_mfma16", "mlt_probe_hbm_read", "mlt_set_timing_events",
                 "mlt_last_kernel", "mlt_query_tiling", "mlt_diag_force_variant",
@@ -34,6 +35,8 @@ _lib = ctypes.CDLL(LIB_PATH)
 _i64, _p, _i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
 _lib.mlt_gemm.restype = _i32
 _lib.mlt_gemm.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _p]
+_lib.mlt_gemm_noalloc.restype = _i32
+_lib.mlt_gemm_noalloc.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _p]
 _lib.mlt_gemm_acc.restype = _i32
 _lib.mlt_gemm_acc.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _i32, _p]
 _lib.mlt_gemm_tiled.restype = _i32
@@ -242,6 +245,20 @@ def mlt_gemm(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor | None = None, tr
                            C.data_ptr(), ldc, dt, _stream(stream))
     if rc != MLT_OK:
         raise MltError(rc, "mlt_gemm")
+    return C
+
+
+def mlt_gemm_noalloc(A: torch.Tensor, B: torch.Tensor, C: torch.Tensor, transB: bool = False,
+                     stream=None) -> torch.Tensor:
+    """mlt_gemm through the entry point that allocates nothing: C must be given."""
+    if C is None:
+        raise ValueError("mlt_gemm_noalloc needs the C it writes (this wrapper allocates nothing)")
+    M, N, K, lda, ldb, ldc, dt, C = _gemm_operands("mlt_gemm_noalloc", A, B, C, transB)
+    with torch.cuda.device(A.device):
+        rc = _lib.mlt_gemm_noalloc(M, N, K, A.data_ptr(), lda, B.data_ptr(), ldb, int(transB),
+                                   C.data_ptr(), ldc, dt, _stream(stream))
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_gemm_noalloc")
     return C
 
 

@@ -764,6 +764,31 @@ float* cached_scratch(int64_t bytes, hipStream_t s) {
 }
 }  // namespace
 
+// The scratch of the entry point that may not allocate (mlt_gemm_noalloc): a fixed array in
+// device memory, one copy per GPU the library runs on, held until the process ends. In host code
+// the array's name is only a handle; its device address is looked up once per device, with that
+// device current, and only that address is ever handed to kernels. Every call on a GPU shares
+// that GPU's array (calls that overlap on one GPU race); nothing in it has to start at zero: each
+// part of a K split writes every element of its slice before the second kernel reads them.
+namespace {
+static __device__ __align__(256) float scratch[kStaticScratchBytes / sizeof(float)];
+constexpr int kMaxDevices = 64;
+float* g_static_scratch[kMaxDevices];
+std::mutex g_static_scratch_mu;
+}  // namespace
+
+float* static_scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+  std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+  if (!g_static_scratch[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return nullptr; }
+    g_static_scratch[dev] = static_cast<float*>(p);
+  }
+  return g_static_scratch[dev];
+}
+
 int run_gemm(const GemmArgs& g_in, const GemmPlan& p, hipStream_t s) {
   GemmArgs g = g_in;
   g.parts = p.parts;

@@ -154,6 +154,30 @@ int mlt_gemm(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const 
   return rc;
 }
 
+int mlt_gemm_noalloc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                     int64_t ldb, int transB, void* C, int64_t ldc, int dtype, void* stream) {
+  int rc = check_gemm(M, N, K, A, lda, B, ldb, transB, C, ldc, dtype);
+  if (rc != MLT_OK) return rc;
+  if (M == 0 || N == 0) return MLT_OK;
+  if (!device_is_gfx950()) return MLT_ERR_DEVICE;
+  GemmArgs g{M, N, K, (const uint16_t*)A, lda, (const uint16_t*)B, ldb, transB ? 1 : 0,
+             (uint16_t*)C, ldc, dtype, forced_gemm_variant(), 0};
+  g.forced_parts = overrides().gemm_parts;
+  GemmPlan p = plan_gemm(g);
+  if (p.parts > 1) {
+    if (p.scratch_bytes > kStaticScratchBytes) return MLT_ERR_SCRATCH;
+    g.scratch = static_scratch_of_current_device();
+    if (!g.scratch) return MLT_ERR_DEVICE;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  {
+    TimedRegion t(s);
+    rc = run_gemm(g, p, s);
+  }
+  if (rc == MLT_OK) note_gemm_kernel(p);
+  return rc;
+}
+
 int mlt_gemm_acc(int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
                  int64_t ldb, int transB, float* C, int64_t ldc, int dtype, void* stream) {
   int rc = check_gemm(M, N, K, A, lda, B, ldb, transB, C, ldc, dtype);
@@ -391,6 +415,7 @@ const char* mlt_status_string(int status) {
     case MLT_ERR_UNSUPPORTED: return "unsupported configuration";
     case MLT_ERR_LAUNCH: return "kernel launch failed";
     case MLT_ERR_DEVICE: return "no usable gfx950 device";
+    case MLT_ERR_SCRATCH: return "the call needs more scratch memory than the no-allocation entry point has";
   }
   return "unknown status";
 }

@@ -54,6 +54,12 @@ struct GemmPlan {
   int mfma_m = 32, mfma_n = 32, mfma_k = 16;
 };
 
+// mlt_gemm_noalloc: bytes of the fixed device array that takes the partial products of a K split
+// across workgroups (no plan the library makes by itself needs more than half of it), and that
+// array's address on the current device (nullptr if it cannot be had)
+constexpr int64_t kStaticScratchBytes = (int64_t)32 << 20;
+float* static_scratch_of_current_device();
+
 GemmPlan plan_gemm(const GemmArgs& g);
 int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s);
 bool gemm_pp_ok(const GemmArgs& g);            // gemm_pp.hip: can the two-group kernel take this problem?
