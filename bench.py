@@ -4,6 +4,8 @@ fp32 accumulate) followed by one non-causal bf16 attention forward B4 H32 S4096 
 the C ABI. Prints one JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W]
+  python bench.py --sweep gemm [--torch] [--sweep-dtype fp16]   markdown table over the GEMM shape families
+  python bench.py --sweep fa2                                    markdown table over the paper's FlashAttention-2 sweep
 
 `value` is the whole step's TFLOP/s (2*M*N*K + 4*B*H*Sq*Sk*D flop per step) with all inputs
 resident in HBM. Each kernel is also timed on its own with HIP events recorded on the launch
@@ -24,15 +26,40 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16/fp16: 256 CUs x 2.4 GHz x 4096 flop/clk/CU
-# HBM-side bytes per launch (fetched + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs summarised under profiles/ (counter x the factor a plain copy of known size gives).
-# Keyed by kernel variant; None when a variant has not been measured.
-MEASURED_TRAFFIC_BYTES = {
-    "mha_fwd_d128_256x64_pp": int((2.0 * 196680 + 131072) * 1024),
-    "gemm_nn_256x256x64_w2x4_pp16": int((2.0 * 786569 + 133228) * 1024),
-}
+# HBM-side bytes per launch (fetched, written) of the step's kernels, as the rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs measured them (counter x the factor that a plain copy of known size
+# gives): a committed text table, one line per kernel name, each with the commit the counters were
+# taken at. A kernel that is not in the table has no measured traffic (null in the JSON line).
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 GEMM_MNK = (8192, 8192, 8192)
 MHA_SHAPE = (4, 32, 4096, 4096, 128)   # B, H, Sq, Sk, D
+
+
+def measured_traffic(kernel, algorithmic_bytes):
+    """{traffic, traffic_source, traffic_ratio} of one kernel from the committed counter table."""
+    none = {"traffic": None, "traffic_source": None, "traffic_ratio": None,
+            "algorithmic_bytes": algorithmic_bytes}
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            lines = [ln.strip() for ln in f if ln.strip() and not ln.lstrip().startswith("#")]
+    except OSError:
+        return none
+    for ln in lines:
+        cols = [c.strip() for c in ln.split("|")]
+        if len(cols) >= 5 and cols[0] == kernel:
+            fetch, write = int(cols[2]), int(cols[3])
+            return {"traffic": fetch + write, "traffic_fetch": fetch, "traffic_write": write,
+                    "traffic_source": "profiles/hbm_traffic.txt: %s, counters taken at commit %s"
+                                      % (cols[1], cols[4]),
+                    "traffic_ratio": (fetch + write) / algorithmic_bytes,
+                    "algorithmic_bytes": algorithmic_bytes}
+    return none
+
+
+def median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
 class HipEvents:
@@ -62,18 +89,22 @@ class HipEvents:
 
 
 def cpu_baseline(A, B, Q, K, V, scale):
-    """Oracle (as it stands) on a bounded sample: GEMM entries at K = 8192 and whole attention rows."""
+    """The oracle as it stands, on the host cores: the two headline problems on a bounded sample
+    (random C entries at K = 8192, whole attention rows) with the time of the full problem
+    extrapolated from it, and two small problems computed in full (GEMM 512^3 with one thread and
+    with all of them, attention B1 H1 S1024 D128)."""
     import numpy as np
     import oracle
     from paper_2503_14985_amd import inputs
     rng = np.random.default_rng(123)
+    nt = oracle.num_threads()               # all host threads; passed explicitly from here on
     M, Kd = A.shape
     N = B.shape[1]
     ns = 4_000_000
     r, c = rng.integers(0, M, ns), rng.integers(0, N, ns)
     Bt = np.ascontiguousarray(B.T)          # same matrix, k-contiguous storage for the inner loop
     t0 = time.perf_counter()
-    oracle.gemm_sampled(A, Bt, r, c, inputs.BF16, transB=True)
+    oracle.gemm_sampled(A, Bt, r, c, inputs.BF16, transB=True, nthreads=nt)
     t_gemm = time.perf_counter() - t0
     f_gemm = 2.0 * Kd * ns
     Bq, H, Sq, D = Q.shape
@@ -81,15 +112,39 @@ def cpu_baseline(A, B, Q, K, V, scale):
     nrows = 49_152
     bs, hs, qs = rng.integers(0, Bq, nrows), rng.integers(0, H, nrows), rng.integers(0, Sq, nrows)
     t0 = time.perf_counter()
-    oracle.mha_fwd_rows(Q, K, V, bs, hs, qs, scale, False, inputs.BF16)
+    oracle.mha_fwd_rows(Q, K, V, bs, hs, qs, scale, False, inputs.BF16, nthreads=nt)
     t_mha = time.perf_counter() - t0
     f_mha = 4.0 * D * Sk * nrows
+
+    # small problems in full
+    a5, b5 = inputs.gemm_inputs(512, 512, 512, inputs.BF16, seed=1)
+    f5 = 2.0 * 512 ** 3
+    t0 = time.perf_counter()
+    oracle.gemm(a5, b5, inputs.BF16, nthreads=1)
+    t5_one = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.gemm(a5, b5, inputs.BF16, nthreads=nt)
+    t5_all = time.perf_counter() - t0
+    q1, k1, v1 = inputs.mha_inputs(1, 1, 1024, 1024, 128, inputs.BF16, seed=1)
+    fm = 4.0 * 1024 * 1024 * 128
+    t0 = time.perf_counter()
+    oracle.mha_fwd(q1, k1, v1, 1.0 / math.sqrt(128), False, inputs.BF16, nthreads=nt)
+    tm = time.perf_counter() - t0
     return {
         "value": (f_gemm + f_mha) / (t_gemm + t_mha) / 1e12, "unit": "TFLOP/s",
-        "cores": oracle.num_threads(), "kind": "oracle",
+        "cores": nt, "kind": "oracle",
         "sample": "%d random C entries of the 8192^3 GEMM (%.1f s) + %d random query rows of the "
                   "B4 H32 S4096 D128 attention (%.1f s), fp64" % (ns, t_gemm, nrows, t_mha),
         "gemm_gflops": f_gemm / t_gemm / 1e9, "mha_gflops": f_mha / t_mha / 1e9,
+        "full_problem_seconds_extrapolated": {
+            "gemm_8192^3": t_gemm * (float(M) * N / ns),
+            "mha_b4_h32_s4096_d128": t_mha * (float(Bq) * H * Sq / nrows),
+            "note": "sample time x (outputs of the full problem / outputs sampled); not run in full"},
+        "small_problems_in_full": {
+            "gemm_512^3_1_thread": {"seconds": t5_one, "gflops": f5 / t5_one / 1e9},
+            "gemm_512^3_all_threads": {"seconds": t5_all, "gflops": f5 / t5_all / 1e9,
+                                       "threads": nt},
+            "mha_b1_h1_s1024_d128_all_threads": {"seconds": tm, "gflops": fm / tm / 1e9}},
     }
 
 
@@ -197,7 +252,8 @@ class PowerSampler:
         import glob
         self.inputs = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") or
                              glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))
-        self.samples, self._stop, self._th = [], False, None
+        self.sclk_files = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.samples, self.clocks, self._stop, self._th = [], [], False, None
 
     @staticmethod
     def _read(path):
@@ -207,6 +263,18 @@ class PowerSampler:
         except (OSError, ValueError):
             return None
 
+    @staticmethod
+    def _current_mhz(path):
+        """The level marked as current in an amdgpu pp_dpm_sclk file ('1: 1650Mhz *')."""
+        try:
+            with open(path) as f:
+                for ln in f:
+                    if ln.rstrip().endswith("*"):
+                        return float(ln.split(":")[1].lower().replace("mhz", "").replace("*", "").strip())
+        except (OSError, ValueError, IndexError):
+            pass
+        return None
+
     def cap_w(self):
         caps = [self._read(os.path.join(os.path.dirname(p), "power1_cap")) for p in self.inputs]
         caps = [c for c in caps if c]
@@ -215,13 +283,19 @@ class PowerSampler:
     def _poll(self):
         while not self._stop:
             vals = [v for v in (self._read(p) for p in self.inputs) if v is not None]
+            now = time.perf_counter()
             if vals:
-                self.samples.append((time.perf_counter(), max(vals) / 1e6))
+                self.samples.append((now, max(vals) / 1e6))
+                # the card being driven is the one drawing the most: take its clock
+                card = self.inputs[vals.index(max(vals))].split("/device/")[0]
+                mhz = self._current_mhz(card + "/device/pp_dpm_sclk")
+                if mhz:
+                    self.clocks.append((now, mhz))
             time.sleep(0.02)
 
     def start(self):
         import threading
-        self.samples, self._stop = [], False
+        self.samples, self.clocks, self._stop = [], [], False
         self._th = threading.Thread(target=self._poll, daemon=True)
         self._th.start()
 
@@ -229,7 +303,8 @@ class PowerSampler:
         self._stop = True
         self._th.join()
         w = [v for (t, v) in self.samples if t >= since]
-        return sum(w) / len(w) if w else None
+        c = [v for (t, v) in self.clocks if t >= since]
+        return (sum(w) / len(w) if w else None), (sum(c) / len(c) if c else None)
 
 
 def power_context(binding, A, B, C, Q, K, V, O, scale):
@@ -269,18 +344,129 @@ def power_context(binding, A, B, C, Q, K, V, O, scale):
                 t_half, n_half = now, n
             if now - t0 >= secs:
                 break
-        watts = ps.stop(t_half)
-        res[name] = {"tflops": flop * (n - n_half) / (now - t_half) / 1e12,
-                     "avg_w": None if watts is None else round(watts, 1)}
-    res["note"] = ("each kernel launched back to back for 1.5 s; rate and board power (hwmon "
-                   "power1_input) over the second half; zeros = all-zero operands of the same shapes")
+        watts, mhz = ps.stop(t_half)
+        tf = flop * (n - n_half) / (now - t_half) / 1e12
+        res[name] = {"tflops": tf, "avg_w": None if watts is None else round(watts, 1),
+                     "sclk_mhz": None if mhz is None else round(mhz, 1),
+                     "frac_mfma_peak": tf / MFMA_PEAK_TFLOPS,
+                     "frac_mfma_peak_at_observed_clock":
+                         None if not mhz else tf / (MFMA_PEAK_TFLOPS * mhz / 2400.0)}
+    res["note"] = ("each kernel launched back to back for 1.5 s; rate, board power (hwmon "
+                   "power1_input) and shader clock (the current level of pp_dpm_sclk) over the "
+                   "second half; zeros = all-zero operands of the same shapes; the fraction at the "
+                   "observed clock is against 256 CUs x 4096 flop/clk x that clock")
     return res
+
+
+GEMM_SWEEP_SHAPES = [
+    # (M, N, K, B stored N x K): the square sweep, the LLM shapes with B stored N x K, mid-size
+    # and decode (skinny) shapes
+    (1024, 1024, 1024, False), (2048, 2048, 2048, False), (3072, 3072, 3072, False),
+    (4096, 4096, 4096, False), (8192, 8192, 8192, False), (8192, 8192, 8192, True),
+    (4096, 14336, 4096, True), (4096, 4096, 14336, True), (8192, 28672, 8192, True),
+    (1024, 4096, 4096, True), (512, 4096, 4096, True), (256, 4096, 4096, True), (128, 4096, 4096, True),
+    (512, 8192, 8192, True), (256, 8192, 8192, True), (256, 14336, 4096, True), (512, 4096, 14336, True),
+    (64, 4096, 4096, True), (64, 14336, 4096, True), (64, 28672, 8192, True), (64, 8192, 28672, True),
+    (64, 131072, 4096, True), (32, 28672, 8192, True), (32, 8192, 28672, True),
+    (16, 4096, 4096, True), (16, 28672, 8192, True), (16, 8192, 28672, True), (16, 131072, 4096, True),
+    (16, 4096, 4096, False), (32, 28672, 8192, False), (1, 28672, 8192, True),
+]
+
+
+def _time_back_to_back(torch, fn, n):
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
+def sweep_gemm(torch, binding, dev, with_torch, dt):
+    """Markdown table of mlt_gemm over the shape families. Each shape is launched back to back
+    (best of two runs of n launches; the library launches on torch's current stream here, so
+    torch's events see it) on torch.randn inputs: N(0,1) for the square shapes, N(0, 0.02^2) for
+    the shapes with B stored N x K. Times below about 12 us are bounded by the Python call."""
+    head = "| M x N x K | B stored | kernel | us | TFLOP/s | GB/s (A+B+C once) |"
+    print(head + (" torch us |" if with_torch else ""))
+    print("|---|---|---|---|---|---|" + ("---|" if with_torch else ""))
+    for (M, N, K, tb) in GEMM_SWEEP_SHAPES:
+        std = 0.02 if (tb or M <= 64) else 1.0
+        A = (torch.randn(M, K, device=dev, dtype=torch.float32) * std).to(dt)
+        B = (torch.randn((N, K) if tb else (K, N), device=dev, dtype=torch.float32) * std).to(dt)
+        C = torch.empty(M, N, device=dev, dtype=dt)
+        n = 20 if M * N * K > 1e11 else 100
+        ms = min(_time_back_to_back(torch, lambda: binding.mlt_gemm(A, B, C=C, transB=tb), n) for _ in range(2))
+        line = "| %d x %d x %d | %s | `%s` | %.1f | %.0f | %.0f |" % (
+            M, N, K, "N x K" if tb else "K x N", binding.mlt_last_kernel(), ms * 1e3,
+            2.0 * M * N * K / ms / 1e9, 2.0 * (M * K + N * K + M * N) / ms / 1e6)
+        if with_torch:
+            tms = min(_time_back_to_back(torch, lambda: torch.matmul(A, B.t() if tb else B, out=C), n)
+                      for _ in range(2))
+            line += " %.1f |" % (tms * 1e3)
+        print(line, flush=True)
+
+
+def sweep_fa2(torch, binding, dev):
+    """Markdown table of mlt_mha_fwd over the shapes of the paper's FlashAttention-2 evaluation
+    (Section 4.2: 32k tokens in total, hidden size 2048 as 32 heads of 64 or 16 heads of 128,
+    with and without the causal mask), N(0,1) inputs; causal rates count visible pairs only."""
+    print("| heads x D | seq | batch | causal | dtype | kernel | ms | TFLOP/s |")
+    print("|---|---|---|---|---|---|---|---|")
+    for (H, D) in [(32, 64), (16, 128)]:
+        for S in [1024, 2048, 4096, 8192, 16384, 32768]:
+            B = 32768 // S
+            for causal in (False, True):
+                for dt in (torch.float16, torch.bfloat16):
+                    if dt == torch.bfloat16 and S not in (4096, 32768):
+                        continue
+                    q = torch.randn(B, H, S, D, device=dev, dtype=dt)
+                    k, v = torch.randn_like(q), torch.randn_like(q)
+                    o = torch.empty_like(q)
+                    flop = 4.0 * B * H * D * (S * (S + 1) / 2 if causal else S * S)
+                    ms = min(_time_back_to_back(
+                        torch, lambda: binding.mlt_mha_fwd(q, k, v, 1 / math.sqrt(D), causal, O=o), 10)
+                        for _ in range(2))
+                    print("| %d x %d | %d | %d | %d | %s | `%s` | %.3f | %.0f |" % (
+                        H, D, S, B, int(causal), "fp16" if dt == torch.float16 else "bf16",
+                        binding.mlt_last_kernel(), ms, flop / ms / 1e9), flush=True)
+
+
+def cold_cache_gemm(binding, ev, dev, sets=3, reps=12):
+    """The 8192^3 GEMM on operand sets that rotate from launch to launch (3 sets of A, B and C,
+    384 MiB each: more than the 256 MiB last-level cache between two uses of the same bytes), so
+    that no launch finds its operands cached by the previous one."""
+    import torch
+    M, N, Kd = GEMM_MNK
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    abc = [(torch.randn((M, Kd), generator=g, device=dev, dtype=torch.bfloat16),
+            torch.randn((Kd, N), generator=g, device=dev, dtype=torch.bfloat16),
+            torch.empty((M, N), device=dev, dtype=torch.bfloat16)) for _ in range(sets)]
+    for i in range(sets):
+        binding.mlt_gemm(abc[i][0], abc[i][1], C=abc[i][2])
+    evs = [(ev.create(), ev.create()) for _ in range(reps)]
+    for i in range(reps):
+        a, b, c = abc[i % sets]
+        binding.mlt_set_timing_events(evs[i][0], evs[i][1])
+        binding.mlt_gemm(a, b, C=c)
+    binding.mlt_set_timing_events(None, None)
+    torch.cuda.synchronize()
+    ms = [ev.elapsed_ms(a, b) for (a, b) in evs]
+    flop = 2.0 * M * N * Kd
+    return {"median_ms": median(ms), "min_ms": min(ms), "tflops_median": flop / median(ms) / 1e9,
+            "frac_mfma_peak": flop / median(ms) / 1e9 / MFMA_PEAK_TFLOPS, "launches": reps,
+            "note": "%d operand sets of 384 MiB used in rotation" % sets}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle timing (used when profiling)")
@@ -293,6 +479,12 @@ def main():
                     help="after the timed steps also run plain device copies of 256 MiB, so a "
                          "counter run (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) can be scaled by "
                          "what the same counter reads for a copy of known size")
+    ap.add_argument("--sweep", choices=["gemm", "fa2"], default=None,
+                    help="instead of the step, time the library over a family of shapes and print "
+                         "a markdown table: the GEMM shape families, or the paper's "
+                         "FlashAttention-2 sweep (Section 4.2)")
+    ap.add_argument("--torch", action="store_true", help="--sweep gemm: add torch.matmul on the same tensors")
+    ap.add_argument("--sweep-dtype", choices=["bf16", "fp16"], default="bf16", help="--sweep gemm: element type")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (kernels on one GPU's share of the "
@@ -311,6 +503,15 @@ def main():
         for _ in range(3):
             dst.copy_(src)          # reads 256 MiB, writes 256 MiB per launch
         torch.cuda.synchronize()
+
+    if args.sweep is not None:
+        torch.manual_seed(0)
+        if args.sweep == "gemm":
+            sweep_gemm(torch, binding, dev, args.torch,
+                       torch.bfloat16 if args.sweep_dtype == "bf16" else torch.float16)
+        else:
+            sweep_fa2(torch, binding, dev)
+        return
 
     if args.only == "paged":
         r = paged_decode(binding, HipEvents(), dev)
@@ -376,18 +577,31 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     value = (f_gemm + f_mha) / (ms_per_step * 1e-3) / 1e12
     gemm_tf, mha_tf = f_gemm / gemm_avg / 1e9, f_mha / mha_avg / 1e9
+    # algorithmic HBM bytes per launch: every operand read once, the result written once
+    b_gemm = 2 * (M * Kd + Kd * N + M * N)
+    b_mha = 2 * Bq * H * D * (2 * Sq + 2 * Sk)
+    t_gemm, t_mha = measured_traffic(names[0], b_gemm), measured_traffic(names[1], b_mha)
 
     # The kernel with the larger share of the step carries the roofline object.
     if mha_avg >= gemm_avg:
-        dom = {"kernel": names[1], "achieved": mha_tf, "avg_ms": mha_avg,
-               "flop_per_launch": f_mha, "traffic": MEASURED_TRAFFIC_BYTES.get(names[1])}
+        dom = {"kernel": names[1], "achieved": mha_tf, "avg_ms": mha_avg, "median_ms": median(mha_ms),
+               "flop_per_launch": f_mha, "t": t_mha}
     else:
-        dom = {"kernel": names[0], "achieved": gemm_tf, "avg_ms": gemm_avg,
-               "flop_per_launch": f_gemm, "traffic": MEASURED_TRAFFIC_BYTES.get(names[0])}
+        dom = {"kernel": names[0], "achieved": gemm_tf, "avg_ms": gemm_avg, "median_ms": median(gemm_ms),
+               "flop_per_launch": f_gemm, "t": t_gemm}
     roofline = {"bound": "mfma", "achieved": dom["achieved"], "peak": MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": dom["achieved"] / MFMA_PEAK_TFLOPS,
-                "traffic": dom["traffic"], "kernel": dom["kernel"], "avg_kernel_ms": dom["avg_ms"],
-                "flop_per_launch": dom["flop_per_launch"]}
+                "traffic": dom["t"]["traffic"], "traffic_source": dom["t"]["traffic_source"],
+                "traffic_ratio": dom["t"]["traffic_ratio"], "kernel": dom["kernel"],
+                "avg_kernel_ms": dom["avg_ms"], "median_kernel_ms": dom["median_ms"],
+                "flop_per_launch": dom["flop_per_launch"],
+                "launches": "the %d timed launches of the step (warm-ups not included), HIP events "
+                            "around each on the launch stream" % args.steps}
+
+    def kernel_line(name, ms, tf, flop, t):
+        return {"kernel": name, "avg_ms": sum(ms) / len(ms), "median_ms": median(ms), "min_ms": min(ms),
+                "tflops": tf, "tflops_median": flop / median(ms) / 1e9,
+                "frac_mfma_peak": tf / MFMA_PEAK_TFLOPS, "hbm": t}
 
     out = {
         "metric": "TFLOP/s + % MFMA peak: bf16 GEMM 8192^3; MHA fwd B4*H32*S4096*D128",
@@ -397,11 +611,9 @@ def main():
         "config": {"workload": "bf16 GEMM M=N=K=8192 row-major A,B (N(0,1), seed 0) + non-causal "
                                "MHA forward B=4 H=32 Sq=Sk=4096 D=128 bf16 (N(0,1), seed 0), "
                                "one of each per step"},
-        "gemm": {"kernel": names[0], "avg_ms": gemm_avg, "min_ms": min(gemm_ms), "tflops": gemm_tf,
-                 "frac_mfma_peak": gemm_tf / MFMA_PEAK_TFLOPS},
-        "mha": {"kernel": names[1], "avg_ms": mha_avg, "min_ms": min(mha_ms), "tflops": mha_tf,
-                "frac_mfma_peak": mha_tf / MFMA_PEAK_TFLOPS,
-                "flop_convention": "4*B*H*Sq*Sk*D"},
+        "gemm": kernel_line(names[0], gemm_ms, gemm_tf, f_gemm, t_gemm),
+        "mha": dict(kernel_line(names[1], mha_ms, mha_tf, f_mha, t_mha),
+                    flop_convention="4*B*H*Sq*Sk*D"),
         "roofline": roofline,
     }
     if not args.no_ceiling:
@@ -409,6 +621,11 @@ def main():
         out["paged_decode"] = paged_decode(binding, ev, dev)
         out["hbm_ceiling"] = hbm_ceiling(binding, ev, dev)
         out["power"] = power_context(binding, A, B, C, Q, K, V, O, scale)
+        for k in ("gemm", "mha"):
+            out[k]["frac_mfma_peak_at_observed_clock"] = out["power"][k + "_n01"]["frac_mfma_peak_at_observed_clock"]
+            out[k]["observed_clock_note"] = ("from the back-to-back run of this kernel in `power` "
+                                             "(its rate over 256 CUs x 4096 flop/clk x the sampled shader clock)")
+        out["gemm_cold_cache"] = cold_cache_gemm(binding, ev, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(A_h, B_h, Q_h, K_h, V_h, scale)
     print(json.dumps(out))

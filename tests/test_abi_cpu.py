@@ -169,10 +169,24 @@ def test_bench_refuses_more_than_one_gpu():
     assert "one GPU" in (r.stderr + r.stdout)
 
 
-def test_sweep_tool_parses_its_arguments():
+def test_bench_offers_the_shape_sweeps():
     import subprocess
     import sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    r = subprocess.run([sys.executable, os.path.join(root, "paper_2503_14985_amd", "sweep.py"), "--help"],
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--help"],
                        capture_output=True, text=True, timeout=120)
-    assert r.returncode == 0 and "fa2" in r.stdout
+    assert r.returncode == 0 and "--sweep" in r.stdout and "fa2" in r.stdout
+
+
+def test_bench_reads_measured_traffic_from_the_committed_table():
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_under_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    assert bench.median([3.0, 1.0, 2.0]) == 2.0 and bench.median([4.0, 1.0, 2.0, 3.0]) == 2.5
+    known = bench.measured_traffic("gemm_nn_256x256x64_w2x4_pp16", 384 << 20)
+    assert known["traffic"] == known["traffic_fetch"] + known["traffic_write"] > 384 << 20
+    assert "commit" in known["traffic_source"] and known["traffic_ratio"] > 1.0
+    unknown = bench.measured_traffic("no_such_kernel", 1)
+    assert unknown["traffic"] is None and unknown["traffic_source"] is None
