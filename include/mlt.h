@@ -17,6 +17,13 @@
  *     rounded to `dtype` with round-to-nearest-even.
  *   - Return value: MLT_OK or a negative mlt_status. No C++ exception crosses the boundary and
  *     nothing aborts. On an error nothing has been enqueued.
+ *   - Device memory of the library's own: the GEMM entry points (few tiles against a long K) and
+ *     mlt_paged_attn_decode (few sequences x heads) may spread one result over several workgroups
+ *     and then keep fp32 partial results in a scratch buffer, one per (device, stream), allocated
+ *     with hipMalloc at the first call that needs it, grown by doubling from 4 MiB (16 MiB covers
+ *     every split the library chooses by itself) and kept until the process ends. Calls on one
+ *     stream are ordered by the stream; calls on different streams use different buffers. If the
+ *     allocation fails the call runs without the split. mlt_gemm_noalloc never allocates.
  */
 #ifndef MLT_H_
 #define MLT_H_
@@ -140,7 +147,9 @@ int mlt_mha_fwd(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const v
  * the seq_lens[b] keys and values of that sequence, which live in fixed-size blocks of a cache:
  *   o = sum_j softmax_j(scale * q . k_j) v_j,   j = 0 .. seq_lens[b] - 1.
  * The keys are split over the wavefronts of a workgroup and the partial maxima, sums and outputs
- * are reduced through LDS (the paper's warp-level decomposition, Listing 6); weights are rounded
+ * are reduced through LDS (the paper's warp-level decomposition, Listing 6); with too few
+ * sequences x heads to fill the chip the keys are split over several workgroups as well, whose
+ * partial results a second kernel merges in a fixed order. Weights are rounded
  * to `dtype` before they multiply V (Listing 5). The paper fixes no storage layout; this one is
  *   Q, O          device, contiguous [B, H, D]
  *   Kc, Vc        device, contiguous [num_blocks, H, block_size, D]: the cache, physical blocks

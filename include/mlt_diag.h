@@ -96,6 +96,14 @@ int mlt_diag_force_variant(const char* gemm_variant, const char* mha_variant);
 int mlt_diag_force_k_parts(int parts);
 
 /*
+ * Number of key ranges per (sequence, head) that mlt_paged_attn_decode spreads over workgroups:
+ * 0 = the library's choice (the default: 1 while sequences x heads alone fill the chip, more
+ * otherwise), 1..64 = that many (ranges beyond the end of a short sequence stay empty).
+ * Process-wide. Returns MLT_OK or MLT_ERR_INVALID_ARG.
+ */
+int mlt_diag_force_key_split(int ranges);
+
+/*
  * Number of workgroups the persistent attention kernel launches (0: one per CU, the default);
  * small values make every workgroup walk through many items even on a small problem. Initial
  * value from MLT_MHA_PS_GRID, read once. Returns MLT_OK or MLT_ERR_INVALID_ARG (negative or

@@ -24,7 +24,7 @@ EXPORTS = ("mlt_gemm", "mlt_gemm_noalloc", "mlt_gemm_acc", "mlt_gemm_tiled", "ml
            "mlt_paged_attn_decode", "mlt_status_string", "mlt_version")
 DIAG_EXPORTS = ("mlt_probe_mfma", "mlt_probe_mfma16", "mlt_probe_hbm_read", "mlt_set_timing_events",
                 "mlt_last_kernel", "mlt_query_tiling", "mlt_diag_force_variant",
-                "mlt_diag_force_k_parts", "mlt_diag_set_persistent_grid")
+                "mlt_diag_force_k_parts", "mlt_diag_force_key_split", "mlt_diag_set_persistent_grid")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -64,6 +64,8 @@ _lib.mlt_diag_force_variant.restype = _i32
 _lib.mlt_diag_force_variant.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
 _lib.mlt_diag_force_k_parts.restype = _i32
 _lib.mlt_diag_force_k_parts.argtypes = [_i32]
+_lib.mlt_diag_force_key_split.restype = _i32
+_lib.mlt_diag_force_key_split.argtypes = [_i32]
 _lib.mlt_diag_set_persistent_grid.restype = _i32
 _lib.mlt_diag_set_persistent_grid.argtypes = [_i32]
 _lib.mlt_status_string.restype = ctypes.c_char_p
@@ -108,6 +110,13 @@ def mlt_diag_force_k_parts(parts: int) -> None:
     rc = _lib.mlt_diag_force_k_parts(int(parts))
     if rc != MLT_OK:
         raise MltError(rc, "mlt_diag_force_k_parts")
+
+
+def mlt_diag_force_key_split(ranges: int) -> None:
+    """Paged decode: 0 = the library's choice; 1..64 = key ranges per (sequence, head)."""
+    rc = _lib.mlt_diag_force_key_split(int(ranges))
+    if rc != MLT_OK:
+        raise MltError(rc, "mlt_diag_force_key_split")
 
 
 def mlt_diag_set_persistent_grid(workgroups: int) -> None:

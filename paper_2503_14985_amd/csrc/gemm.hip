@@ -740,6 +740,8 @@ ScratchSlot g_scratch[kScratchSlots];
 int g_scratch_used = 0;
 std::mutex g_scratch_mu;
 
+}  // namespace
+
 float* cached_scratch(int64_t bytes, hipStream_t s) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
@@ -762,7 +764,6 @@ float* cached_scratch(int64_t bytes, hipStream_t s) {
   slot->bytes = want;
   return slot->ptr;
 }
-}  // namespace
 
 // The scratch of the entry point that may not allocate (mlt_gemm_noalloc): a fixed array in
 // device memory, one copy per GPU the library runs on, held until the process ends. In host code

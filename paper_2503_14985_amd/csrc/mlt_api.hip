@@ -287,13 +287,19 @@ int mlt_paged_attn_decode(int64_t B, int64_t H, int64_t D, int64_t block_size, i
   if (!device_is_gfx950()) return MLT_ERR_DEVICE;
   PagedArgs a{B, H, D, block_size, max_blocks, num_blocks, (const uint16_t*)Q, (const uint16_t*)Kc,
               (const uint16_t*)Vc, block_table, seq_lens, (uint16_t*)O, scale, dtype};
+  a.forced_split = overrides().key_split;
   hipStream_t s = (hipStream_t)stream;
-  int rc;
+  int rc, nsplit = 1;
   {
     TimedRegion t(s);
-    rc = run_paged_decode(a, s);
+    rc = run_paged_decode(a, s, &nsplit);
   }
-  if (rc == MLT_OK) g_last_kernel = D == 128 ? "paged_decode_d128_w4" : "paged_decode_d64_w4";
+  if (rc == MLT_OK) {
+    static thread_local char name[48];
+    if (nsplit > 1) snprintf(name, sizeof name, "paged_decode_d%d_w4_keysplit%d", (int)D, nsplit);
+    else snprintf(name, sizeof name, "paged_decode_d%d_w4", (int)D);
+    g_last_kernel = name;
+  }
   return rc;
 }
 
@@ -367,6 +373,12 @@ int mlt_diag_force_variant(const char* gemm_variant, const char* mha_variant) {
 int mlt_diag_force_k_parts(int parts) {
   if (parts != 0 && parts != 1 && parts != 2 && parts != 4 && parts != 8) return MLT_ERR_INVALID_ARG;
   overrides().gemm_parts = parts;
+  return MLT_OK;
+}
+
+int mlt_diag_force_key_split(int ranges) {
+  if (ranges < 0 || ranges > 64) return MLT_ERR_INVALID_ARG;
+  overrides().key_split = ranges;
   return MLT_OK;
 }
 

@@ -103,7 +103,7 @@ int run_mha_ps(const MhaArgs& a, hipStream_t s);
 // Process-wide overrides of the automatic kernel choice, for tuning and for the tests that must
 // reach every kernel (mlt_diag_force_variant; initial values from MLT_GEMM_VARIANT /
 // MLT_MHA_VARIANT / MLT_MHA_PS_GRID, read once).
-struct Overrides { int gemm = GEMM_AUTO; int gemm_parts = 0; int mha = MHA_AUTO; int ps_grid = 0; };
+struct Overrides { int gemm = GEMM_AUTO; int gemm_parts = 0; int mha = MHA_AUTO; int ps_grid = 0; int key_split = 0; };
 Overrides& overrides();
 // Device facts the launchers need, cached per thread for the current device.
 struct DeviceInfo { int ncu = 0; bool gfx950 = false; };
@@ -123,7 +123,14 @@ struct PagedArgs {
   uint16_t* O;
   float scale;
   int dtype;
+  int forced_split = 0;      // > 0: ranges of keys per (sequence, head), from mlt_diag_force_key_split
 };
-int run_paged_decode(const PagedArgs& a, hipStream_t s);   // paged.hip
+// paged.hip; *nsplit_out: the number of key ranges per (sequence, head) that ran
+int run_paged_decode(const PagedArgs& a, hipStream_t s, int* nsplit_out);
+
+// The library's own scratch memory for a stream of the current device: at least `bytes`, kept
+// (and grown by doubling) from call to call, never freed; nullptr if it cannot be had. Work of
+// one stream that uses it is ordered by the stream.
+float* cached_scratch(int64_t bytes, hipStream_t s);
 
 }  // namespace mlt

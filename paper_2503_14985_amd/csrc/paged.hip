@@ -13,6 +13,12 @@
 // nothing is exchanged between lanes except the D/8-lane sum of a dot product. All partial
 // results (16 or 32 per workgroup) meet once, in LDS, at the end.
 //
+// With fewer (sequence, head) pairs than the chip needs workgroups, the same split goes one level
+// up as well: the units of a sequence are cut into `nsplit` contiguous ranges, one workgroup per
+// (sequence, head, range); each leaves its maximum, sum and unnormalised output slice (fp32) in a
+// scratch buffer, and a second small kernel merges the ranges of a pair in index order, the way
+// the workgroup merges its own partial results.
+//
 // The operation is bound by reading the cache once from HBM (2 * seq_len * D * 2 bytes per
 // sequence and head), so there is no MFMA here (a 1-row product would waste it) and no LDS staging:
 // 16-byte loads go straight to registers, one unit ahead of the arithmetic. Products use the
@@ -55,12 +61,14 @@ template <> struct Dot2<f16_tag> {
   }
 };
 
-template <typename Tag, int D>
+// SPLIT: blockIdx.y is the range of units this workgroup takes, and the result goes to `part`
+// ([pair][range][2 + D] floats: maximum (log2 domain), sum, unnormalised outputs) instead of O.
+template <typename Tag, int D, bool SPLIT>
 __global__ __launch_bounds__(PG_NT) void paged_decode_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kc,
     const uint16_t* __restrict__ Vc, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ seq_lens, uint16_t* __restrict__ O, int H, int block_size,
-    int max_blocks, int num_blocks, float c) {
+    const int32_t* __restrict__ seq_lens, uint16_t* __restrict__ O, float* __restrict__ part, int H,
+    int block_size, int max_blocks, int num_blocks, float c) {
   constexpr int LPR = D / 8;                 // lanes per key row (16 bytes each)
   constexpr int RPI = 64 / LPR;              // key rows per load instruction
   constexpr int NL = PG_UNIT / RPI;          // loads per unit and matrix
@@ -76,8 +84,17 @@ __global__ __launch_bounds__(PG_NT) void paged_decode_kernel(
   int len = seq_lens[b];
   const int cap = max_blocks * block_size;
   len = len < 1 ? 1 : (len > cap ? cap : len);           // never trust it further than the table
-  const int nunits = (len + PG_UNIT - 1) / PG_UNIT;
+  const int all_units = (len + PG_UNIT - 1) / PG_UNIT;
   const int upb = block_size / PG_UNIT;                  // units per cache block
+  // the units this workgroup takes: all of them, or its range of a cut into gridDim.y ranges of
+  // equal length (a multiple of the wavefront count; the last ranges of a short sequence are empty)
+  int u_begin = 0, nunits = all_units;
+  if (SPLIT) {
+    const int nsplit = (int)gridDim.y;
+    const int per = ((all_units + nsplit - 1) / nsplit + PG_NW - 1) / PG_NW * PG_NW;
+    u_begin = (int)blockIdx.y * per;
+    nunits = u_begin + per < all_units ? u_begin + per : all_units;
+  }
 
   // this lane's 8 query elements, as packed pairs
   const u32x4 qv = *reinterpret_cast<const u32x4_mem*>(Q + (int64_t)bh * D + chunk * 8);
@@ -105,9 +122,9 @@ __global__ __launch_bounds__(PG_NT) void paged_decode_kernel(
   for (int e = 0; e < 8; ++e) o[e] = 0.f;
 
   u32x4 kf[2][NL], vf[2][NL];
-  if (wave < nunits) load_unit(wave, kf[0], vf[0]);
+  if (u_begin + wave < nunits) load_unit(u_begin + wave, kf[0], vf[0]);
   int cur = 0;
-  for (int u = wave; u < nunits; u += PG_NW) {
+  for (int u = u_begin + wave; u < nunits; u += PG_NW) {
     if (u + PG_NW < nunits) {
       if (cur == 0) load_unit(u + PG_NW, kf[1], vf[1]); else load_unit(u + PG_NW, kf[0], vf[0]);
     }
@@ -161,32 +178,92 @@ __global__ __launch_bounds__(PG_NT) void paged_decode_kernel(
     float M = sm[0];
 #pragma unroll
     for (int s = 1; s < NSPLIT; ++s) M = __builtin_fmaxf(M, sm[s]);
+    // a range past the end of a short sequence saw no key at all: its sum and outputs are zeros
+    // (the weights below must not become exp2(-inf - -inf))
+    const float Mref = SPLIT && M == -__builtin_inff() ? 0.f : M;
     float L = 0.f, acc = 0.f;
 #pragma unroll
     for (int s = 0; s < NSPLIT; ++s) {
-      const float wgt = __builtin_amdgcn_exp2f(sm[s] - M);       // empty groups: exp2(-inf) = 0
+      const float wgt = __builtin_amdgcn_exp2f(sm[s] - Mref);    // empty groups: exp2(-inf) = 0
       L += sl[s] * wgt;
       acc += so[s][tid] * wgt;
     }
-    O[(int64_t)bh * D + tid] = Elem<Tag>::from_f32(acc / L);
+    if (SPLIT) {
+      float* out = part + ((int64_t)bh * gridDim.y + blockIdx.y) * (2 + D);
+      if (tid == 0) { out[0] = M; out[1] = L; }
+      out[2 + tid] = acc;
+    } else {
+      O[(int64_t)bh * D + tid] = Elem<Tag>::from_f32(acc / L);
+    }
   }
 }
 
+// One workgroup of D threads per (sequence, head): the ranges' partial results, in index order.
+// Range 0 is never empty (a sequence has at least one key), so the maximum is finite.
 template <typename Tag, int D>
-int launch_paged(const PagedArgs& a, hipStream_t s) {
+__global__ __launch_bounds__(D) void paged_merge_kernel(const float* __restrict__ part,
+                                                        uint16_t* __restrict__ O, int nsplit) {
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const float* p = part + (int64_t)bh * nsplit * (2 + D);
+  float M = p[0];
+  for (int s = 1; s < nsplit; ++s) M = __builtin_fmaxf(M, p[s * (2 + D)]);
+  float L = 0.f, acc = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const float wgt = __builtin_amdgcn_exp2f(p[s * (2 + D)] - M);   // empty ranges: exp2(-inf) = 0
+    L += p[s * (2 + D) + 1] * wgt;
+    acc += p[s * (2 + D) + 2 + tid] * wgt;
+  }
+  O[(int64_t)bh * D + tid] = Elem<Tag>::from_f32(acc / L);
+}
+
+template <typename Tag, int D>
+int launch_paged(const PagedArgs& a, int nsplit, float* part, hipStream_t s) {
   const float c = a.scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((paged_decode_kernel<Tag, D>), dim3((unsigned)(a.B * a.H)), dim3(PG_NT), 0, s,
-                     a.Q, a.Kc, a.Vc, a.block_table, a.seq_lens, a.O, (int)a.H, (int)a.block_size,
-                     (int)a.max_blocks, (int)a.num_blocks, c);
+  const unsigned pairs = (unsigned)(a.B * a.H);
+  if (nsplit <= 1) {
+    hipLaunchKernelGGL((paged_decode_kernel<Tag, D, false>), dim3(pairs), dim3(PG_NT), 0, s,
+                       a.Q, a.Kc, a.Vc, a.block_table, a.seq_lens, a.O, (float*)nullptr, (int)a.H,
+                       (int)a.block_size, (int)a.max_blocks, (int)a.num_blocks, c);
+    return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL((paged_decode_kernel<Tag, D, true>), dim3(pairs, (unsigned)nsplit), dim3(PG_NT), 0, s,
+                     a.Q, a.Kc, a.Vc, a.block_table, a.seq_lens, a.O, part, (int)a.H,
+                     (int)a.block_size, (int)a.max_blocks, (int)a.num_blocks, c);
+  if (hipGetLastError() != hipSuccess) return MLT_ERR_LAUNCH;
+  hipLaunchKernelGGL((paged_merge_kernel<Tag, D>), dim3(pairs), dim3(D), 0, s, part, a.O, nsplit);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
 }  // namespace
 
-int run_paged_decode(const PagedArgs& a, hipStream_t s) {
+// Ranges per (sequence, head): 1 while the pairs alone give every CU a workgroup; otherwise what
+// brings the launch to two workgroups per CU, as long as a range of the longest possible sequence
+// (the table's width) keeps at least 16 units (256 keys), and at most 32 (measured on 8 to 256
+// pairs of 2k to 32k keys: more ranges than that lose to their own start and end).
+int plan_paged_split(const PagedArgs& a) {
+  if (a.forced_split > 0) return a.forced_split > 64 ? 64 : a.forced_split;
+  DeviceInfo di;
+  const int64_t ncu = device_info(di) ? di.ncu : 256;
+  const int64_t pairs = a.B * a.H;
+  if (pairs > ncu) return 1;
+  const int64_t max_units = (a.max_blocks * a.block_size + PG_UNIT - 1) / PG_UNIT;
+  int64_t n = (2 * ncu + pairs - 1) / pairs;
+  if (n > max_units / 16) n = max_units / 16;
+  if (n > 32) n = 32;
+  return n < 1 ? 1 : (int)n;
+}
+
+int run_paged_decode(const PagedArgs& a, hipStream_t s, int* nsplit_out) {
+  int nsplit = plan_paged_split(a);
+  float* part = nullptr;
+  if (nsplit > 1) {
+    part = cached_scratch(a.B * a.H * nsplit * (2 + a.D) * (int64_t)sizeof(float), s);
+    if (!part) nsplit = 1;                               // no scratch to be had: the plain form
+  }
+  if (nsplit_out) *nsplit_out = nsplit;
   if (a.dtype == MLT_BF16)
-    return a.D == 128 ? launch_paged<bf16_tag, 128>(a, s) : launch_paged<bf16_tag, 64>(a, s);
-  return a.D == 128 ? launch_paged<f16_tag, 128>(a, s) : launch_paged<f16_tag, 64>(a, s);
+    return a.D == 128 ? launch_paged<bf16_tag, 128>(a, nsplit, part, s) : launch_paged<bf16_tag, 64>(a, nsplit, part, s);
+  return a.D == 128 ? launch_paged<f16_tag, 128>(a, nsplit, part, s) : launch_paged<f16_tag, 64>(a, nsplit, part, s);
 }
 
 }  // namespace mlt

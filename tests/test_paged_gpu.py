@@ -153,3 +153,55 @@ def test_bench_size_sampled_heads():
         worst = max(worst, float(err))
     print("   sampled max err %.3g" % worst, flush=True)
     assert worst <= TOL[BF16]
+
+
+@pytest.fixture
+def key_split():
+    """Forces the number of key ranges per (sequence, head) for one test, then restores the
+    library's own choice."""
+    from paper_2503_14985_amd import binding
+    yield binding.mlt_diag_force_key_split
+    binding.mlt_diag_force_key_split(0)
+
+
+@pytest.mark.parametrize("nsplit", [2, 3, 7, 64])
+@pytest.mark.parametrize("dtype,D", [(BF16, 128), (FP16, 64)])
+def test_key_split_across_workgroups(key_split, nsplit, dtype, D):
+    """Keys cut into ranges over several workgroups, merged by the second kernel: lengths from one
+    key (every range but the first empty) to ranges that end inside a unit, a block and a wavefront
+    round."""
+    from paper_2503_14985_amd import binding
+    key_split(nsplit)
+    lens = [1, 2, 16, 17, 63, 65, 100, 257, 1000, 1023, 2048, 3001]
+    _check(len(lens), 3, D, 16, lens, dtype, seed=11)
+    assert binding.mlt_last_kernel().endswith("_keysplit%d" % nsplit)
+    _check(2, 2, D, 64, [4096, 777], dtype, seed=12)
+
+
+def test_key_split_is_chosen_for_few_long_sequences_and_repeats_bit_for_bit(key_split):
+    from paper_2503_14985_amd import binding
+    key_split(0)
+    q, kc, vc, table, lens, _, _ = inputs.paged_inputs(2, 4, 128, 16, [16384, 9000], BF16, 13)
+    scale = 1.0 / math.sqrt(128)
+    O1 = _run(q, kc, vc, table, lens, scale, BF16)
+    assert "_keysplit" in binding.mlt_last_kernel(), binding.mlt_last_kernel()
+    O2 = _run(q, kc, vc, table, lens, scale, BF16)
+    assert torch.equal(O1, O2)                              # fixed merge order: no run-to-run change
+    t = table.copy()
+    t[t >= kc.shape[0]] = 0
+    ref = oracle.paged_attn_decode(q, kc, vc, t, lens, scale, BF16)
+    assert np.abs(O1.double().cpu().numpy() - ref).max() <= TOL[BF16]
+    # many pairs: the plain form
+    _check(40, 32, 128, 16, [100] * 40, BF16, seed=14)
+    assert "_keysplit" not in binding.mlt_last_kernel()
+
+
+def test_key_split_single_key_and_block_placement(key_split):
+    key_split(5)
+    q, kc, vc, table, lens, kd, vd = inputs.paged_inputs(3, 4, 128, 16, [1, 33, 2000], BF16, 4)
+    O = _run(q, kc, vc, table, lens, 0.2, BF16)
+    assert np.array_equal(inputs.torch_to_bits(O)[0], vd[0][:, 0, :])          # one key: O = V[0] exactly
+    perm = np.random.default_rng(9).permutation(kc.shape[0])
+    inv = np.argsort(perm)
+    O3 = _run(q, kc[perm], vc[perm], inv[table].astype(np.int32), lens, 0.2, BF16)
+    assert torch.equal(O3, O)
