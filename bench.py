@@ -213,34 +213,59 @@ def hbm_ceiling(binding, ev, dev):
             "note": "read-only streaming kernel over 2 GiB, 16-byte loads, 32 KB pieces round-robin over 8 workgroups per CU"}
 
 
+def sustained(torch, fn, flop_per_call, secs=1.5, batch=25):
+    """fn launched back to back for `secs` seconds; rate, board power and shader clock over the
+    second half of the run."""
+    ps = PowerSampler()
+    for _ in range(5):
+        fn()
+    torch.cuda.synchronize()
+    ps.start()
+    t0 = time.perf_counter()
+    n, t_half, n_half = 0, None, 0
+    while True:
+        for _ in range(batch):
+            fn()
+        torch.cuda.synchronize()
+        n += batch
+        now = time.perf_counter()
+        if t_half is None and now - t0 >= secs / 2:
+            t_half, n_half = now, n
+        if now - t0 >= secs:
+            break
+    watts, mhz = ps.stop(t_half)
+    tf = flop_per_call * (n - n_half) / (now - t_half) / 1e12
+    return {"tflops": tf, "avg_w": None if watts is None else round(watts, 1),
+            "sclk_mhz": None if mhz is None else round(mhz, 1),
+            "pj_per_flop": None if watts is None else round(watts / tf, 4),
+            "frac_mfma_peak": tf / MFMA_PEAK_TFLOPS,
+            "frac_mfma_peak_at_observed_clock":
+                None if not mhz else tf / (MFMA_PEAK_TFLOPS * mhz / 2400.0)}
+
+
 def mfma_ceiling(binding, ev, A, dev):
-    """Rate of a register-only MFMA loop over the whole chip (mlt_probe_mfma) on all-zero operands
-    and on the GEMM's own N(0,1) operand values: the second is what the chip's power management
-    leaves of the nominal peak for such data, before any memory traffic. Context for `roofline`,
-    whose `peak` stays the nominal one."""
+    """Rate, board power and clock of a register-only MFMA loop over the whole chip
+    (mlt_probe_mfma), each run for a second: on all-zero operands, and on the GEMM's own N(0,1)
+    operand values through both MFMA shapes. The N(0,1) figures are what the chip's power
+    management leaves of the nominal peak for such data before any memory traffic; board power
+    over rate is the energy per flop of the multipliers alone, to set beside the kernels' own
+    (`power`). Context for `roofline`, whose `peak` stays the nominal one."""
     import torch
     sink = torch.zeros(16, dtype=torch.float32, device=dev)
     res = {}
     for name, data, size in (("zeros", torch.zeros(1 << 16, dtype=torch.bfloat16, device=dev), 32),
+                             ("zeros_16x16x32", torch.zeros(1 << 16, dtype=torch.bfloat16, device=dev), 16),
                              ("n01", A.reshape(-1)[: 1 << 16].contiguous(), 32),
                              ("n01_16x16x32", A.reshape(-1)[: 1 << 16].contiguous(), 16)):
-        iters, reps = 2048, 12
-        for _ in range(3):
-            binding.mlt_probe_mfma(iters, data, sink, size)
-        e0, e1 = ev.create(), ev.create()
-        binding.mlt_set_timing_events(e0, None)
+        iters = 2048
         flop = binding.mlt_probe_mfma(iters, data, sink, size)
-        binding.mlt_set_timing_events(None, None)
-        for _ in range(reps - 2):
-            binding.mlt_probe_mfma(iters, data, sink, size)
-        binding.mlt_set_timing_events(None, e1)
-        binding.mlt_probe_mfma(iters, data, sink, size)
-        binding.mlt_set_timing_events(None, None)
-        torch.cuda.synchronize()
-        res[name + "_tflops"] = flop * reps / (ev.elapsed_ms(e0, e1) * 1e-3) / 1e12
-    res["note"] = ("register-only bf16 MFMA loop, 8 wavefronts per CU; zeros / n01: 32x32x16 MFMAs on "
-                   "all-zero operands / on operands taken from the GEMM's A matrix; n01_16x16x32: the "
-                   "same N(0,1) operands through 16x16x32 MFMAs (the GEMM kernel's shape)")
+        r = sustained(torch, lambda: binding.mlt_probe_mfma(iters, data, sink, size), flop, secs=1.0, batch=10)
+        res[name + "_tflops"] = r["tflops"]
+        res[name] = r
+    res["note"] = ("register-only bf16 MFMA loop, 8 wavefronts per CU, launched back to back for 1 s "
+                   "(rate, board power, shader clock over the second half); zeros / n01: 32x32x16 "
+                   "MFMAs on all-zero operands / on operands taken from the GEMM's A matrix; "
+                   "_16x16x32: the same through 16x16x32 MFMAs (the GEMM kernel's shape)")
     return res
 
 
@@ -326,35 +351,13 @@ def power_context(binding, A, B, C, Q, K, V, O, scale):
             ("mha_n01", lambda: binding.mlt_mha_fwd(Q, K, V, scale, causal=False, O=O), f_mha),
             ("mha_zeros", lambda: binding.mlt_mha_fwd(Qz, Kz, Vz, scale, causal=False, O=O), f_mha))
     res = {"cap_w": ps.cap_w()}
-    secs = 1.5
     for name, fn, flop in runs:
-        for _ in range(5):
-            fn()
-        torch.cuda.synchronize()
-        ps.start()
-        t0 = time.perf_counter()
-        n, t_half, n_half = 0, None, 0
-        while True:
-            for _ in range(25):
-                fn()
-            torch.cuda.synchronize()
-            n += 25
-            now = time.perf_counter()
-            if t_half is None and now - t0 >= secs / 2:
-                t_half, n_half = now, n
-            if now - t0 >= secs:
-                break
-        watts, mhz = ps.stop(t_half)
-        tf = flop * (n - n_half) / (now - t_half) / 1e12
-        res[name] = {"tflops": tf, "avg_w": None if watts is None else round(watts, 1),
-                     "sclk_mhz": None if mhz is None else round(mhz, 1),
-                     "frac_mfma_peak": tf / MFMA_PEAK_TFLOPS,
-                     "frac_mfma_peak_at_observed_clock":
-                         None if not mhz else tf / (MFMA_PEAK_TFLOPS * mhz / 2400.0)}
+        res[name] = sustained(torch, fn, flop)
     res["note"] = ("each kernel launched back to back for 1.5 s; rate, board power (hwmon "
                    "power1_input) and shader clock (the current level of pp_dpm_sclk) over the "
                    "second half; zeros = all-zero operands of the same shapes; the fraction at the "
-                   "observed clock is against 256 CUs x 4096 flop/clk x that clock")
+                   "observed clock is against 256 CUs x 4096 flop/clk x that clock; pj_per_flop = "
+                   "board power / rate")
     return res
 
 

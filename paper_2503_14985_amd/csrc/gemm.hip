@@ -19,27 +19,6 @@
 namespace mlt {
 
 // ------------------------------------------------------------------------------------------
-// Workgroup id -> C tile. Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each
-// with its own L2. First undo that so every XCD owns one contiguous range of logical ids, then
-// walk logical ids in column-major order inside bands of GROUP_M tile rows, so that the
-// workgroups resident on one XCD at a time share A row panels and B column panels.
-// ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void tile_of_block(int bid, int nbm, int nbn, int& tm, int& tn) {
-  constexpr int NXCD = 8, GROUP_M = 8;
-  const int total = nbm * nbn;
-  const int q = total / NXCD, rem = total % NXCD;
-  const int xcd = bid % NXCD, idx = bid / NXCD;
-  const int logical = xcd * q + (xcd < rem ? xcd : rem) + idx;
-  const int per_group = GROUP_M * nbn;
-  const int g = logical / per_group;
-  const int first_m = g * GROUP_M;
-  const int rows = (nbm - first_m) < GROUP_M ? (nbm - first_m) : GROUP_M;
-  const int in_g = logical % per_group;
-  tm = first_m + in_g % rows;
-  tn = in_g / rows;
-}
-
-// ------------------------------------------------------------------------------------------
 // Main kernel. Requirements checked by the host: K % 8 == 0, lda % 8 == 0, ldb % 8 == 0,
 // N % 8 == 0 when B is K x N row-major, A and B 16-byte aligned. M, N and K need not be
 // multiples of the tile: out-of-range rows are clamped on load (their products land in
@@ -83,7 +62,7 @@ template <typename Tag, int BM, int BN, int BK, int WM, int WN, bool TRANSB, int
 __global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
     int M, int N, int K_, const uint16_t* __restrict__ A_, int64_t lda,
     const uint16_t* __restrict__ B_, int64_t ldb, uint16_t* __restrict__ C_, int64_t ldc, int nbm,
-    int nbn, int epi, const uint16_t* __restrict__ bias, int part_steps, int64_t part_stride) {
+    int nbn, int nxcd, int epi, const uint16_t* __restrict__ bias, int part_steps, int64_t part_stride) {
   typedef GemmTile<Tag, BM, BN, BK, WM, WN, TRANSB> Cfg;
   typedef typename Elem<Tag>::vec8 V8;
   extern __shared__ __align__(16) char smem_all[];
@@ -109,7 +88,7 @@ __global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
   const int wm = wave / WN, wn = wave % WN;
   char* const smem = smem_all + kg * Cfg::SMEM;
   int tile_m, tile_n;
-  tile_of_block(blockIdx.x, nbm, nbn, tile_m, tile_n);
+  tile_of_block<8>(blockIdx.x, nbm, nbn, nxcd, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   // ---- per-thread staging assignments (fixed for the whole K loop)
@@ -512,7 +491,7 @@ static int launch_tile(const GemmArgs& g, hipStream_t s) {
   const int nbm = (int)((g.M + BM - 1) / BM), nbn = (int)((g.N + BN - 1) / BN);
   if (g.parts <= 1) {
     hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(Cfg::NT * KS), KS * Cfg::SMEM, s, (int)g.M, (int)g.N,
-                       (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.epi(), g.bias, 0,
+                       (int)g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, device_xcds(), g.epi(), g.bias, 0,
                        (int64_t)0);
     return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
   }
@@ -523,7 +502,7 @@ static int launch_tile(const GemmArgs& g, hipStream_t s) {
   const int64_t part_stride = g.M * g.N;
   hipLaunchKernelGGL(kern, dim3(nbm * nbn, parts), dim3(Cfg::NT * KS), KS * Cfg::SMEM, s, (int)g.M,
                      (int)g.N, (int)g.K, g.A, g.lda, g.B, g.ldb, reinterpret_cast<uint16_t*>(g.scratch),
-                     g.N, nbm, nbn, (int)EPI_PART32, (const uint16_t*)nullptr, part_steps, part_stride);
+                     g.N, nbm, nbn, device_xcds(), (int)EPI_PART32, (const uint16_t*)nullptr, part_steps, part_stride);
   if (hipGetLastError() != hipSuccess) return MLT_ERR_LAUNCH;
   const int64_t nthreads = g.M * ((g.N + 3) / 4);
   hipLaunchKernelGGL(gemm_splitk_reduce_kernel<Tag>, dim3((unsigned)((nthreads + 255) / 256)), dim3(256),

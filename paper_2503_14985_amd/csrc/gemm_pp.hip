@@ -51,7 +51,6 @@ constexpr int PP_SMEM = PP_NSLOT * PP_SLOT;              // 160 KB
 static_assert(PP_A_BYTES == PP_SLOT && PP_B_BYTES == PP_SLOT, "one tile per slot");
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
 constexpr int WAIT_LGKM0 = 0xC07F;       // lgkmcnt(0)
@@ -60,37 +59,11 @@ constexpr int WAIT_VM0 = 0x0F70;         // vmcnt(0)
 constexpr int WAIT_VM8 = 0x0F78;         // vmcnt(8)
 constexpr int WAIT_VM8_LGKM0 = 0x0078;   // vmcnt(8) lgkmcnt(0)
 
-// Workgroup id -> C tile. Ids go round-robin over the 8 XCDs, so each XCD gets a contiguous range
-// of the tile sequence (its 32 resident workgroups share one L2), and the sequence walks the tiles
-// in bands of GROUP_M tile rows, column by column: an XCD's 32 tiles form a 4 x 8 block that shares
-// 4 row panels of A and 8 column panels of B. (Measured at 8192^3: bands of 4 rows 0.8 % faster
-// than bands of 8 with B stored K x N, 2.4 % with B stored N x K; 2, 5, 6 rows slower, 32 rows
-// -5 %.)
-__device__ __forceinline__ void tile_of_block_pp(int bid, int nbm, int nbn, int& tm, int& tn) {
-  constexpr int NXCD = 8, GROUP_M = 4;
-  const int total = nbm * nbn;
-  const int q = total / NXCD, rem = total % NXCD;
-  const int xcd = bid % NXCD, idx = bid / NXCD;
-  const int logical = xcd * q + (xcd < rem ? xcd : rem) + idx;
-  const int per_group = GROUP_M * nbn;
-  const int g = logical / per_group;
-  const int first_m = g * GROUP_M;
-  const int rows = (nbm - first_m) < GROUP_M ? (nbm - first_m) : GROUP_M;
-  const int in_g = logical % per_group;
-  tm = first_m + in_g % rows;
-  tn = in_g / rows;
-}
-
-// 16 bytes per lane from global memory (uniform base + per-lane byte offset) straight into LDS at
-// lds_addr + 16 * lane. Written as inline assembly on purpose: the compiler orders every LDS read
-// after a preceding LDS-writing load it knows of (s_waitcnt vmcnt(0)), which would serialise the
-// pipeline; here the ordering is established by the explicit waits and barriers of the schedule.
-__device__ __forceinline__ void load_lds16(const char* base, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(base)
-               : "memory", "m0");
-}
+// Workgroup id -> C tile: bands of 4 tile rows, column by column, so an XCD's 32 resident
+// workgroups form a 4 x 8 block of tiles that shares 4 row panels of A and 8 column panels of B.
+// (Measured at 8192^3: bands of 4 rows 0.8 % faster than bands of 8 with B stored K x N, 2.4 % with
+// B stored N x K; 2, 5, 6 rows slower, 32 rows -5 %.)
+constexpr int PP_GROUP_M = 4;
 
 // Swizzle of the K x N operand tile ([64 k][32 chunks of 8 n]): chunk q of row k sits in slot
 // q ^ swz_kn(k). A transposing read serves 32 lanes at a time (8 bytes each). With 32-wide tiles
@@ -114,7 +87,7 @@ template <typename Tag, bool TRANSB, int MS>
 __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
-    int nbn, int epi, const uint16_t* __restrict__ bias) {
+    int nbn, int nxcd, int epi, const uint16_t* __restrict__ bias) {
   typedef typename Elem<Tag>::vec8 V8;
   extern __shared__ __align__(16) char smem[];
 
@@ -123,7 +96,7 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   const int wm = wave >> 2, wn = wave & 3;               // 2 x 4 wavefronts of 128 x 64
   const int grp = wm;                                    // waves 0-3 / 4-7: one of each per SIMD
   int tile_m, tile_n;
-  tile_of_block_pp(blockIdx.x, nbm, nbn, tile_m, tile_n);
+  tile_of_block<PP_GROUP_M>(blockIdx.x, nbm, nbn, nxcd, tile_m, tile_n);
   const int m0 = tile_m * PP_BM, n0 = tile_n * PP_BN;
 
   // ---- global -> LDS assignments. A tile is 32 blocks of 1 KB (64 lanes x 16 bytes). The four
@@ -267,8 +240,8 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     if (KT > 1) { issue_loads(1, 3); __builtin_amdgcn_s_waitcnt(WAIT_VM8); }
     else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
   }
-  __builtin_amdgcn_s_barrier();
-  if (grp == 1) __builtin_amdgcn_s_barrier();
+  MLT_BARRIER();
+  if (grp == 1) MLT_BARRIER();
 
   int slot_a = 0;                                         // slot of A_k; B_k is in the next one
   for (int k = 0; k < KT; ++k) {
@@ -288,7 +261,7 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
         issue_loads(k + 1, slot_a + 3 >= PP_NSLOT ? slot_a + 3 - PP_NSLOT : slot_a + 3);
       __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
     __builtin_amdgcn_sched_barrier(0);
     // ---- compute phase
 #pragma unroll
@@ -299,11 +272,11 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
         for (int j = 0; j < TB; ++j) acc[i][j] = mfma_ms<MS>(af[kk][i], bf[kk][j], acc[i][j]);
     __builtin_amdgcn_sched_barrier(0);
     if (grp == 0) __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
     __builtin_amdgcn_sched_barrier(0);
     slot_a = slot_a + 2 >= PP_NSLOT ? slot_a + 2 - PP_NSLOT : slot_a + 2;
   }
-  if (grp == 0) __builtin_amdgcn_s_barrier();
+  if (grp == 0) MLT_BARRIER();
 
   // ---- epilogue: fp32 -> 16-bit (RNE) and store, or add to the fp32 C; guarded per element
   // accumulator register r of a 32x32 tile is row 8*(r/4) + 4*(l/32) + r%4, of a 16x16 tile row
@@ -383,7 +356,7 @@ static int launch_pp(const GemmArgs& g, hipStream_t s) {
   }
   const int nbm = (int)((g.M + PP_BM - 1) / PP_BM), nbn = (int)((g.N + PP_BN - 1) / PP_BN);
   hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(PP_NT), PP_SMEM, s, (int)g.M, (int)g.N, (int)g.K,
-                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.epi(), g.bias);
+                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, device_xcds(), g.epi(), g.bias);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 

@@ -180,15 +180,6 @@ struct SdCfg {
   static constexpr int J = KS / 32 / 4;          // k chunks per computing wavefront and stage
 };
 
-constexpr int sd_wait_imm(int vm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (15 << 8); }
-
-__device__ __forceinline__ void sd_load_lds16(const void* base, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(base)
-               : "memory", "m0");
-}
-
 template <typename Tag, int MT>
 __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
@@ -231,7 +222,7 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
         const int nrow = n0 + r < N ? r : N - 1 - n0;      // clamped: such columns are never stored
         int ck = (lane % L::LPR) ^ (r & 15);               // the 16-byte chunk this lane fetches
         if (k0 + ck * 8 >= K) ck = 0;                      // past K (last stage): any valid chunk, zeroed later
-        sd_load_lds16(Bw, (uint32_t)nrow * (uint32_t)ldb * 2u + (uint32_t)(k0 + ck * 8) * 2u,
+        load_lds16(Bw, (uint32_t)nrow * (uint32_t)ldb * 2u + (uint32_t)(k0 + ck * 8) * 2u,
                       slot + (uint32_t)ii * 1024u);
       }
       ++i_g;
@@ -253,15 +244,15 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
         // issued so far: stages 0 .. min(G, g + SD_ST - 1) - 1; those after g may stay in flight
         const int last = g + SD_ST - 2 < G - 1 ? g + SD_ST - 2 : G - 1;
         switch (last - g) {
-          case 0: __builtin_amdgcn_s_waitcnt(sd_wait_imm(0)); break;
-          case 1: __builtin_amdgcn_s_waitcnt(sd_wait_imm(4)); break;
-          case 2: __builtin_amdgcn_s_waitcnt(sd_wait_imm(8)); break;
-          case 3: __builtin_amdgcn_s_waitcnt(sd_wait_imm(12)); break;
-          case 4: __builtin_amdgcn_s_waitcnt(sd_wait_imm(16)); break;
-          case 5: __builtin_amdgcn_s_waitcnt(sd_wait_imm(20)); break;
-          default: __builtin_amdgcn_s_waitcnt(sd_wait_imm(24)); break;
+          case 0: __builtin_amdgcn_s_waitcnt(wait_imm(0, 15)); break;
+          case 1: __builtin_amdgcn_s_waitcnt(wait_imm(4, 15)); break;
+          case 2: __builtin_amdgcn_s_waitcnt(wait_imm(8, 15)); break;
+          case 3: __builtin_amdgcn_s_waitcnt(wait_imm(12, 15)); break;
+          case 4: __builtin_amdgcn_s_waitcnt(wait_imm(16, 15)); break;
+          case 5: __builtin_amdgcn_s_waitcnt(wait_imm(20, 15)); break;
+          default: __builtin_amdgcn_s_waitcnt(wait_imm(24, 15)); break;
         }
-        __builtin_amdgcn_s_barrier();                      // stage g is complete in LDS for everyone
+        MLT_BARRIER();                      // stage g is complete in LDS for everyone
         issue_next();                                      // stage g + SD_ST - 1, into the slot of stage g-1 (read before this barrier)
       }
       // end of a group: the barriers of the computing wavefronts' reductions (two per block and
@@ -309,7 +300,7 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
 #pragma unroll
         for (int gb = 0; gb < GB; ++gb) {
           if (gb < nb) {
-            __builtin_amdgcn_s_barrier();
+            MLT_BARRIER();
             const uint32_t slot = lds0 + (uint32_t)(g % SD_ST) * SD_STAGE_B;
             u32x4 bf[J][NT];
 #pragma unroll

@@ -38,41 +38,13 @@ constexpr int W4_SLOT = 32768;                           // one operand tile
 constexpr int W4_NSLOT = 5;
 constexpr int W4_SMEM = W4_NSLOT * W4_SLOT;              // 160 KB
 
-typedef __attribute__((address_space(3))) void* lptr4_t;
-
-// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
-constexpr int w4_wait(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
-
-__device__ __forceinline__ void tile_of_block_w4(int bid, int nbm, int nbn, int& tm, int& tn) {
-  constexpr int NXCD = 8, GROUP_M = 8;
-  const int total = nbm * nbn;
-  const int q = total / NXCD, rem = total % NXCD;
-  const int xcd = bid % NXCD, idx = bid / NXCD;
-  const int logical = xcd * q + (xcd < rem ? xcd : rem) + idx;
-  const int per_group = GROUP_M * nbn;
-  const int g = logical / per_group;
-  const int first_m = g * GROUP_M;
-  const int rows = (nbm - first_m) < GROUP_M ? (nbm - first_m) : GROUP_M;
-  const int in_g = logical % per_group;
-  tm = first_m + in_g % rows;
-  tn = in_g / rows;
-}
-
-// see gemm_pp.hip: inline assembly so that the schedule's own waits order these loads
-__device__ __forceinline__ void w4_load_lds16(const char* base, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(base)
-               : "memory", "m0");
-}
-
 }  // namespace
 
 template <typename Tag, bool TRANSB>
 __global__ __launch_bounds__(W4_NT) void gemm_w4_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
-    int nbn, int epi, const uint16_t* __restrict__ bias) {
+    int nbn, int nxcd, int epi, const uint16_t* __restrict__ bias) {
   typedef typename Elem<Tag>::vec8 V8;
   extern __shared__ __align__(16) char smem[];
 
@@ -80,7 +52,7 @@ __global__ __launch_bounds__(W4_NT) void gemm_w4_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;               // 2 x 2 wavefronts of 128 x 128
   int tile_m, tile_n;
-  tile_of_block_w4(blockIdx.x, nbm, nbn, tile_m, tile_n);
+  tile_of_block<8>(blockIdx.x, nbm, nbn, nxcd, tile_m, tile_n);
   const int m0 = tile_m * W4_BM, n0 = tile_n * W4_BN;
 
   // ---- global -> LDS assignments: a tile is 32 blocks of 1 KB; wavefront w fills blocks 8w ..
@@ -118,19 +90,19 @@ __global__ __launch_bounds__(W4_NT) void gemm_w4_kernel(
     }
   }
   const int KT = K / W4_BK;
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr4_t)smem;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
   // Load i (0..7) of this wavefront's share of A_t (operand tile 2t) or B_t (operand tile 2t+1).
   // Tiles past the last K step are fetched all the same (from the last step's addresses, into
   // the slot they would have had, which nobody reads any more): the loop then needs no branch
   // between its MFMAs and every wait count is the same in every step.
   auto issue_a = [&](int t, int i) {
     const int ts = t < KT ? t : KT - 1;
-    w4_load_lds16(a_base + (int64_t)ts * (W4_BK * 2), voff_a[i],
+    load_lds16(a_base + (int64_t)ts * (W4_BK * 2), voff_a[i],
                   lds0 + (uint32_t)((2 * t) % W4_NSLOT) * W4_SLOT + wave * 8192 + i * 1024);
   };
   auto issue_b = [&](int t, int i) {
     const int ts = t < KT ? t : KT - 1;
-    w4_load_lds16(b_base + (int64_t)ts * b_kstep, voff_b[i],
+    load_lds16(b_base + (int64_t)ts * b_kstep, voff_b[i],
                   lds0 + (uint32_t)((2 * t + 1) % W4_NSLOT) * W4_SLOT + wave * 8192 + i * 1024);
   };
 
@@ -196,8 +168,8 @@ __global__ __launch_bounds__(W4_NT) void gemm_w4_kernel(
   for (int i = 0; i < 8; ++i) issue_a(1, i);
 #pragma unroll
   for (int i = 0; i < 8; ++i) issue_b(1, i);
-  __builtin_amdgcn_s_waitcnt(w4_wait(16, 15));
-  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_s_waitcnt(wait_imm(16, 15));
+  MLT_BARRIER();
   W4_SB();
 #pragma unroll
   for (int i = 0; i < 4; ++i) read_a(0, 0, i, fa[0][i]);
@@ -215,8 +187,8 @@ __global__ __launch_bounds__(W4_NT) void gemm_w4_kernel(
       if (kk == 3) {
         // tile k has been read completely (slice 3 sits in registers once lgkmcnt is 0); my loads
         // of tile k+1 must have landed; behind them only A_{k+2} may still be in flight
-        __builtin_amdgcn_s_waitcnt(w4_wait(8, 0));
-        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_s_waitcnt(wait_imm(8, 0));
+        MLT_BARRIER();
         W4_SB();
       }
 #pragma unroll
@@ -255,7 +227,7 @@ __global__ __launch_bounds__(W4_NT) void gemm_w4_kernel(
     sb = sb_n;
   }
 #undef W4_SB
-  __builtin_amdgcn_s_waitcnt(w4_wait(0, 0));              // the surplus loads of the last steps
+  __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));              // the surplus loads of the last steps
 
   // ---- epilogue: fp32 -> 16-bit (RNE) and store, or the other epilogue forms; guarded per element
   const int row_base = m0 + wm * 128 + 4 * h;
@@ -291,7 +263,7 @@ static int launch_w4(const GemmArgs& g, hipStream_t s) {
   }
   const int nbm = (int)((g.M + W4_BM - 1) / W4_BM), nbn = (int)((g.N + W4_BN - 1) / W4_BN);
   hipLaunchKernelGGL(kern, dim3(nbm * nbn), dim3(W4_NT), W4_SMEM, s, (int)g.M, (int)g.N, (int)g.K,
-                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, g.epi(), g.bias);
+                     g.A, g.lda, g.B, g.ldb, g.C, g.ldc, nbm, nbn, device_xcds(), g.epi(), g.bias);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 

@@ -41,7 +41,7 @@ template <typename Tag, int D, bool CAUSAL>
 __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int Sq, int Sk, int nq, int total,
-    float c, int negate) {
+    int nxcd, float c, int negate) {
   typedef PaCfg<D> L;
   typedef typename Elem<Tag>::vec8 V8;
   constexpr int NKK = L::NKK, NDT = L::NDT, ROWB = L::ROWB;
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
   const int grp = wave >> 2;                             // waves w and w+4 share a SIMD
   const int lq = lane & 31, h = lane >> 5;
   int bh, qt;
-  block_map(blockIdx.x, total, nq, bh, qt);
+  block_map(blockIdx.x, total, nq, nxcd, bh, qt);
   const int q0 = qt * PA_BM + wave * 32;                 // first query row of this wavefront
   const int my_q = q0 + lq;
 
@@ -260,8 +260,8 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
   if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 15));
   else if (nblk == 2) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
   else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
-  __builtin_amdgcn_s_barrier();
-  if (grp == 1) __builtin_amdgcn_s_barrier();            // stagger: group 1 runs one phase behind
+  MLT_BARRIER();
+  if (grp == 1) MLT_BARRIER();            // stagger: group 1 runs one phase behind
 
   // prologue: S_0 = K_0 Q^T, then the first two V_0 groups (a compute phase without the P V part)
   {
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
       if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
       else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
   }
 
   int slot_off = 0;                                       // byte offset of tile j's slot
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
     } else {
       __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
     __builtin_amdgcn_sched_barrier(0);
     // (measured: with D = 128 the MFMA phase gains 3 % from a raised issue priority, D = 64 loses)
     if (D == 128) __builtin_amdgcn_s_setprio(1);
@@ -367,12 +367,12 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp_kernel(
       if (j + 3 < nblk) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
       else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
     __builtin_amdgcn_sched_barrier(0);
     slot_off = slot_off_next;
   }
 #undef MLT_SB
-  if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
+  if (grp == 0) MLT_BARRIER();            // same barrier count for both groups
 
   // ---- epilogue: O = O^T / l, l summed over both key halves; 8 consecutive d per lane and piece
   const float l_tot = both_halves_sum(l_run);
@@ -431,7 +431,7 @@ template <typename Tag, int D>
 __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int Sq, int Sk, int nq, int total,
-    float c, int negate) {
+    int nxcd, float c, int negate) {
   typedef PaCfg<D> L;
   typedef typename Elem<Tag>::vec8 V8;
   constexpr int NKK = L::NKK, NDT = L::NDT, ROWB = L::ROWB;
@@ -494,7 +494,7 @@ __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
   const char *pf_k, *pf_v;
   {
     int b0, t0;
-    block_map(pf_item, total, nq, b0, t0);
+    block_map(pf_item, total, nq, nxcd, b0, t0);
     pf_k = Kb + (int64_t)b0 * head_b;
     pf_v = Vb + (int64_t)b0 * head_b;
   }
@@ -529,7 +529,7 @@ __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
       pf_item += G;
       if (pf_item < total) {
         int b2, t2;
-        block_map(pf_item, total, nq, b2, t2);
+        block_map(pf_item, total, nq, nxcd, b2, t2);
         pf_k = Kb + (int64_t)b2 * head_b;
         pf_v = Vb + (int64_t)b2 * head_b;
       }
@@ -672,7 +672,7 @@ __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
   // ---- start of the stream: Q of the first item, the first tiles, S_0 (as in mha_pp_kernel)
   int item = (int)blockIdx.x;                 // the item being computed
   int bh, qt;
-  block_map(item, total, nq, bh, qt);
+  block_map(item, total, nq, nxcd, bh, qt);
   int q0 = qt * PA_BM + wave * 32;
   int o_bh = bh, o_q0 = q0;                   // the item the accumulators belong to
 #pragma unroll
@@ -682,8 +682,8 @@ __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
   for (int t = 0; t < PA_AHEAD; ++t) issue_next();
   if (NT >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 15));
   else __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));     // NT >= 2
-  __builtin_amdgcn_s_barrier();
-  if (grp == 1) __builtin_amdgcn_s_barrier();            // stagger: group 1 runs one phase behind
+  MLT_BARRIER();
+  if (grp == 1) MLT_BARRIER();            // stagger: group 1 runs one phase behind
   q_finish();
   {
 #pragma unroll
@@ -705,7 +705,7 @@ __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
       if (NT >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
       else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
   }
 
   // ---- the stream of key tiles: softmax phase X, compute phase C per tile. j is the tile's number
@@ -722,7 +722,7 @@ __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
     // g-2, the finished O tile (at an item's first tile), then the softmax of S_g
     if (last) {
       item += G;
-      block_map(item, total, nq, bh, qt);
+      block_map(item, total, nq, nxcd, bh, qt);
       q0 = qt * PA_BM + wave * 32;
       q_issue(bh, q0);
     }
@@ -752,7 +752,7 @@ __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
     } else {
       __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
     MLT_SB();
     if (D == 128) __builtin_amdgcn_s_setprio(1);
     // ---- C: O^T += V_g^T P_g^T, then S^T of stream tile g+1 (after the last tile of an item that
@@ -809,14 +809,14 @@ __global__ __launch_bounds__(PA_NT, 1) void mha_ps_kernel(
         wait_vm15(n);
       }
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
     MLT_SB();
     slot_off = slot_off_next;
     ++st_age;
     j = j + 1 == nblk ? 0 : j + 1;
   }
 #undef MLT_SB
-  if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
+  if (grp == 0) MLT_BARRIER();            // same barrier count for both groups
   store_item(o_bh, o_q0);
 }
 
@@ -853,7 +853,7 @@ template <typename Tag, int D, bool CAUSAL>
 __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp16_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ V, uint16_t* __restrict__ O, int Sq, int Sk, int nq, int total,
-    float c, int negate) {
+    int nxcd, float c, int negate) {
   typedef PaCfg<D> L;
   typedef typename Elem<Tag>::vec8 V8;
   constexpr int NDS = D / 32;                            // 32-deep d slices of S^T = K Q^T
@@ -866,7 +866,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp16_kernel(
   const int grp = wave >> 2;                             // waves w and w+4 share a SIMD
   const int l16 = lane & 15, g4 = lane >> 4;
   int bh, qt_wg;
-  block_map(blockIdx.x, total, nq, bh, qt_wg);
+  block_map(blockIdx.x, total, nq, nxcd, bh, qt_wg);
   const int q0 = qt_wg * PA_BM + wave * 32;              // first query row of this wavefront
   int my_q[2];
   my_q[0] = q0 + l16;
@@ -1070,8 +1070,8 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp16_kernel(
   if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(2 * LPT, 15));
   else if (nblk == 2) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
   else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
-  __builtin_amdgcn_s_barrier();
-  if (grp == 1) __builtin_amdgcn_s_barrier();            // stagger: group 1 runs one phase behind
+  MLT_BARRIER();
+  if (grp == 1) MLT_BARRIER();            // stagger: group 1 runs one phase behind
 
   // prologue: S_0 = K_0 Q^T, then the first two V_0 chunks
   {
@@ -1096,7 +1096,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp16_kernel(
       if (nblk >= 3) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
       else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
   }
 
   int slot_off = 0;                                       // byte offset of tile j's slot
@@ -1123,7 +1123,7 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp16_kernel(
     } else {
       __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
     __builtin_amdgcn_sched_barrier(0);
     if (D == 128) __builtin_amdgcn_s_setprio(1);
     // ---- C_j: O^T += V_j^T P_j^T (V chunks 0..3), then S_{j+1}^T = K_{j+1} Q^T (K chunks 0..3),
@@ -1171,12 +1171,12 @@ __global__ __launch_bounds__(PA_NT, D == 64 ? 4 : 1) void mha_pp16_kernel(
       if (j + 3 < nblk) __builtin_amdgcn_s_waitcnt(wait_imm(LPT, 15));
       else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
     }
-    __builtin_amdgcn_s_barrier();
+    MLT_BARRIER();
     __builtin_amdgcn_sched_barrier(0);
     slot_off = slot_off_next;
   }
 #undef MLT_SB
-  if (grp == 0) __builtin_amdgcn_s_barrier();            // same barrier count for both groups
+  if (grp == 0) MLT_BARRIER();            // same barrier count for both groups
 
   // ---- epilogue: O = O^T / l, l summed over the four lane groups; 4 consecutive d per store
 #pragma unroll
@@ -1219,7 +1219,7 @@ int launch_mha_pp(const MhaArgs& a, hipStream_t s) {
   float c = (a.scale < 0 ? -a.scale : a.scale) * LOG2E;
   if (c < 1e-30f) c = 1e-30f;
   hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(PA_NT), L::SMEM, s, a.Q, a.K, a.V, a.O,
-                     (int)a.Sq, (int)a.Sk, nq, (int)total, c, a.scale < 0 ? 1 : 0);
+                     (int)a.Sq, (int)a.Sk, nq, (int)total, device_xcds(), c, a.scale < 0 ? 1 : 0);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 
@@ -1254,7 +1254,7 @@ int launch_mha_ps(const MhaArgs& a, hipStream_t s) {
   float c = (a.scale < 0 ? -a.scale : a.scale) * LOG2E;   // c > 0 always, as in launch_mha_pp
   if (c < 1e-30f) c = 1e-30f;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(PA_NT), L::SMEM, s, a.Q, a.K, a.V, a.O,
-                     (int)a.Sq, (int)a.Sk, nq, (int)total, c, a.scale < 0 ? 1 : 0);
+                     (int)a.Sq, (int)a.Sk, nq, (int)total, device_xcds(), c, a.scale < 0 ? 1 : 0);
   return hipGetLastError() == hipSuccess ? MLT_OK : MLT_ERR_LAUNCH;
 }
 

@@ -14,21 +14,6 @@ constexpr int PA_NS = 5;      // LDS ring slots (two-group kernels)
 constexpr int PA_AHEAD = 3;   // tiles fetched ahead of the softmax phase that issues the fetch
 constexpr float PA_LAZY_T = 8.f;   // log2 units a row maximum may grow before the reference point moves
 
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
-constexpr int wait_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
-
-// 16 bytes per lane from global memory (uniform base + per-lane byte offset) straight into LDS at
-// lds_addr + 16 * lane. Inline assembly on purpose: the compiler would order every later LDS read
-// behind such a load (s_waitcnt vmcnt(0)); here the schedule's explicit waits and barriers do it.
-__device__ __forceinline__ void load_lds16(const void* base, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(base)
-               : "memory", "m0");
-}
-
 // max / sum of a per-lane value with the one held by lane l ^ 32 (the other half of the keys of
 // the same query): permlane32_swap fed the same register twice returns both halves' values.
 __device__ __forceinline__ float both_halves_max(float x) {
@@ -62,14 +47,11 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return __builtin_fmaxf(__builtin_fmaxf(a, b), c);       // v_max3_f32
 }
 
-// Workgroup id -> (batch*head, query tile): undo the round-robin of ids over the 8 XCDs so each
-// XCD owns a contiguous range, then walk the query tiles of one head, last tile first (with the
-// causal mask it has the most work). All tiles of a head share one XCD's L2.
-__device__ __forceinline__ void block_map(int bid, int total, int nq, int& bh, int& qt) {
-  constexpr int NXCD = 8;
-  const int q = total / NXCD, rem = total % NXCD;
-  const int xcd = bid % NXCD, idx = bid / NXCD;
-  const int logical = xcd * q + (xcd < rem ? xcd : rem) + idx;
+// Workgroup id -> (batch*head, query tile): every XCD owns a contiguous range of the items, and
+// the query tiles of one head are walked last tile first (with the causal mask it has the most
+// work). All tiles of a head share one XCD's L2.
+__device__ __forceinline__ void block_map(int bid, int total, int nq, int nxcd, int& bh, int& qt) {
+  const int logical = logical_block(bid, total, nxcd);
   bh = logical / nq;
   qt = nq - 1 - logical % nq;
 }

@@ -78,10 +78,18 @@ bool device_info(DeviceInfo& out) {
     if (hipGetDeviceProperties(&p, dev) != hipSuccess) { (void)hipGetLastError(); return false; }
     cached.gfx950 = strncmp(p.gcnArchName, "gfx950", 6) == 0;
     cached.ncu = p.multiProcessorCount;
+    int xcds = 0;
+    if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess) (void)hipGetLastError();
+    cached.nxcd = xcds > 0 ? xcds : 8;
     cached_dev = dev;
   }
   out = cached;
   return true;
+}
+
+int device_xcds() {
+  DeviceInfo d;
+  return device_info(d) && d.nxcd > 0 ? d.nxcd : 8;
 }
 
 }  // namespace mlt
@@ -122,6 +130,7 @@ int check_mha(int64_t B, int64_t H, int64_t Sq, int64_t Sk, int64_t D, const voi
   auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   if (!al16(Q) || !al16(K) || !al16(V) || !al16(O)) return MLT_ERR_INVALID_ARG;
   if (Sq > INT_MAX || Sk > INT_MAX || B * H > INT_MAX) return MLT_ERR_UNSUPPORTED;
+  if (Sk * D * 2 >= ((int64_t)1 << 31)) return MLT_ERR_UNSUPPORTED;   // 32-bit offsets inside one head's K
   return MLT_OK;
 }
 

@@ -25,6 +25,65 @@ typedef u32x2 __attribute__((may_alias)) u32x2_mem;
 
 #define MLT_LDS __attribute__((address_space(3)))
 
+// Workgroup barrier of the pipelined kernels (the ones that order their direct-to-LDS loads with
+// hand-counted s_waitcnt values). In the debug build (-DMLT_DEBUG_BARRIERS, libmlt_dbg.so) every
+// such barrier first waits for ALL of the wavefront's outstanding memory operations and is taken
+// twice, which changes the timing of every hand-off and makes any wait count that is too lax
+// harmless there: since every result is a fixed function of the inputs (fixed summation orders),
+// the two builds must agree bit for bit, and a tile read before it has landed, or a slot
+// overwritten while still being read, shows as a difference between them.
+#ifdef MLT_DEBUG_BARRIERS
+#define MLT_BARRIER()                                                   \
+  do {                                                                  \
+    __builtin_amdgcn_s_waitcnt(0x0070); /* vmcnt(0) lgkmcnt(0) */       \
+    __builtin_amdgcn_s_barrier();                                       \
+    __builtin_amdgcn_s_barrier();                                       \
+  } while (0)
+#else
+#define MLT_BARRIER() __builtin_amdgcn_s_barrier()
+#endif
+
+typedef __attribute__((address_space(3))) void* lptr_t;   // cast of a __shared__ pointer to its LDS byte address
+
+// s_waitcnt immediate (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4] left at its maximum,
+// lgkmcnt [11:8]); vm = 63 / lgkm = 15 leave that counter alone
+constexpr int wait_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
+
+// 16 bytes per lane from global memory (uniform base + per-lane byte offset) straight into LDS at
+// lds_addr + 16 * lane. Inline assembly on purpose: the compiler would order every later LDS read
+// behind such a load (s_waitcnt vmcnt(0)), which would serialise the pipelines built on it; the
+// kernels' own explicit waits and barriers establish the ordering instead.
+__device__ __forceinline__ void load_lds16(const void* base, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(base)
+               : "memory", "m0");
+}
+
+// Workgroup ids are dealt round-robin to the chip's XCDs (nxcd of them, from the device
+// attributes), each with its own L2. This undoes the deal: XCD x owns one contiguous range of the
+// `total` logical ids, so that workgroups that share operands can be made to share an L2.
+__device__ __forceinline__ int logical_block(int bid, int total, int nxcd) {
+  const int q = total / nxcd, rem = total % nxcd;
+  const int xcd = bid % nxcd, idx = bid / nxcd;
+  return xcd * q + (xcd < rem ? xcd : rem) + idx;
+}
+
+// Workgroup id -> C tile: logical ids walk the tiles in column-major order inside bands of GROUP_M
+// tile rows, so that the workgroups resident on one XCD at a time share A row panels and B column
+// panels.
+template <int GROUP_M>
+__device__ __forceinline__ void tile_of_block(int bid, int nbm, int nbn, int nxcd, int& tm, int& tn) {
+  const int logical = logical_block(bid, nbm * nbn, nxcd);
+  const int per_group = GROUP_M * nbn;
+  const int g = logical / per_group;
+  const int first_m = g * GROUP_M;
+  const int rows = (nbm - first_m) < GROUP_M ? (nbm - first_m) : GROUP_M;
+  const int in_g = logical % per_group;
+  tm = first_m + in_g % rows;
+  tn = in_g / rows;
+}
+
 struct bf16_tag {};
 struct f16_tag {};
 

@@ -106,8 +106,11 @@ int run_mha_ps(const MhaArgs& a, hipStream_t s);
 struct Overrides { int gemm = GEMM_AUTO; int gemm_parts = 0; int mha = MHA_AUTO; int ps_grid = 0; int key_split = 0; };
 Overrides& overrides();
 // Device facts the launchers need, cached per thread for the current device.
-struct DeviceInfo { int ncu = 0; bool gfx950 = false; };
+struct DeviceInfo { int ncu = 0; int nxcd = 0; bool gfx950 = false; };
 bool device_info(DeviceInfo& out);
+// XCDs of the current device (hipDeviceAttributeNumberOfXccs; 8, the MI355X's, if it cannot be
+// read). Only the workgroup -> tile maps use it: a wrong value costs L2 hits, never correctness.
+int device_xcds();
 
 // probe.hip: launches the register-only MFMA loop, returns the flop it will execute (< 0: launch failed)
 double run_mfma_probe(int iters, int nblocks, const void* data, float* sink, int mfma_size, hipStream_t s);
