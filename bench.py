@@ -624,6 +624,11 @@ def main():
         out["paged_decode"] = paged_decode(binding, ev, dev)
         out["hbm_ceiling"] = hbm_ceiling(binding, ev, dev)
         out["power"] = power_context(binding, A, B, C, Q, K, V, O, scale)
+        # second number beside the nominal fraction: against what a register-only loop of the same
+        # MFMA shape reaches on N(0,1) operands on this board (power management included)
+        for k, ceil in (("gemm", "n01_16x16x32"), ("mha", "n01")):
+            out[k]["frac_of_measured_mfma_ceiling"] = out[k]["tflops"] / out["mfma_ceiling"][ceil + "_tflops"]
+            out[k]["measured_mfma_ceiling"] = "mfma_ceiling.%s_tflops" % ceil
         for k in ("gemm", "mha"):
             out[k]["frac_mfma_peak_at_observed_clock"] = out["power"][k + "_n01"]["frac_mfma_peak_at_observed_clock"]
             out[k]["observed_clock_note"] = ("from the back-to-back run of this kernel in `power` "

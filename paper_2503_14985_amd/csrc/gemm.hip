@@ -544,9 +544,9 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   // 8 K steps: 0.60, 0.41, 0.35); ties go to the larger tile. (3072^3, 144 big tiles: 1033 TFLOP/s
   // against 739 with 576 tiles of 128x128; 2048^3, 64 big tiles: 437 against 758; 256 x 4096 x
   // 4096: 482 with 256 split tiles of 64x64, 326 unsplit, 244 with 64 tiles of 128x128.)
-  // Never less than the time the operands take to arrive: A and B once, at 5.2 TB/s when every CU
-  // has a workgroup pulling (measured: 64 x 8192 x 28672 in 91 us), proportionally less with fewer
-  // workgroups than CUs (the same problem on 128 workgroups: 154 us).
+  // Never less than the time the operands take to arrive (A and B once at 5.2 TB/s: 64 x 8192 x
+  // 28672 measured 91 us), more when too few workgroups pull or the last round leaves CUs idle
+  // (the term is spelled out in the code below).
   // On top of that the K steps may be split over 2, 4 or 8 workgroups per tile (the small-tile
   // kernels), when the tiles alone leave most of the chip idle against a long K: each part writes
   // an fp32 partial tile to a scratch and a second kernel adds the parts in a fixed order
@@ -560,8 +560,13 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     const int64_t rounds = (wgs + NCU - 1) / NCU;
     const int64_t steps = (KT + parts - 1) / parts;
     const int64_t compute = rounds * steps * t_step;
-    const int64_t pulling = wgs < NCU ? wgs : NCU;
-    const int64_t arrive = (g.M + g.N) * g.K * 2 * NCU / (5200 * pulling);
+    // operand arrival: both operands once at 5.2 TB/s, which about 0.6 workgroups per CU already
+    // draw (measured 37 GB/s per streaming workgroup: 64 of them 2.4 TB/s, 128 4.2, 224 5.7);
+    // beyond one workgroup per CU the last round's idle CUs count (448 workgroups take the time
+    // of 512: 32 x 28672 x 8192 measured 104-108 us on 64 x 64 tiles against 82 on 224 of 64 x 128)
+    const int64_t base = (g.M + g.N) * g.K * 2 / 5200;
+    const int64_t need = 6 * NCU / 10;
+    const int64_t arrive = wgs >= NCU ? base * rounds * NCU / wgs : (wgs >= need ? base : base * need / wgs);
     return (compute > arrive ? compute : arrive) + (parts > 1 ? 4000 + 2 * parts * g.M * g.N / 1000 : 0);
   };
   // Among the candidates within 8 % of the best estimate the largest tile wins, then the fewest
