@@ -578,13 +578,29 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   const Cand split[] = {{GEMM_128_K2, 128, 128, 575}, {GEMM_64X128_K2, 64, 128, 370}, {GEMM_64_K4, 64, 64, 220}};
   const Cand whole[] = {{GEMM_128_W8, 128, 128, 600}, {GEMM_64X128_W8, 64, 128, 410}, {GEMM_64_W4, 64, 64, 350}};
   struct Choice { int variant, parts, area; int64_t t; };
-  Choice all[16];
+  Choice all[20];
   int n_all = 0;
   // no tile taller or wider than the matrix rounded up to 64 (it would multiply padding)
   auto fits = [&](int bm, int bn) {
     return !(bm > 64 && bm > (g.M + 63) / 64 * 64) && !(bn > 64 && bn > (g.N + 63) / 64 * 64);
   };
   if (g.forced_parts <= 1 && fits(256, 256)) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 1)};
+  // The two-group kernel on 128 x 128 tiles (two workgroups per CU, no K split across workgroups).
+  // Measured per K step and tile: 0.47 us with a second workgroup on the CU, 0.52 us alone, and
+  // about 5 us more than the register-staged kernels before the first and after the last step.
+  // 2048 x 4096 x 4096 (512 tiles): 64 us against 73 on 128 big tiles and 86 on the K-split
+  // 128 x 128 kernel; 1024 x 8192 x 8192: 121 against 134 and 161; with one tile per CU it wins
+  // from about 128 K steps on (512 x 8192 x 8192: 76 against 82), ties at 64 (1024 x 4096 x 4096:
+  // 42.8 against 42.5; 256 x 14336 x 4096: 43.9 against 40.8) and loses to the shorter start
+  // below (2048^3: 27.6 against 25.9).
+  if (pp && g.forced_parts <= 1 && fits(128, 128)) {
+    const int64_t wgs = ((g.M + 127) / 128) * ((g.N + 127) / 128);
+    const int64_t own = wgs <= NCU ? KT * 518 : ((wgs + NCU - 1) / NCU) * KT * 470;
+    const int64_t base = (g.M + g.N) * g.K * 2 / 5200;
+    const int64_t need = 6 * NCU / 10;
+    const int64_t arrive = wgs >= need ? base : base * need / wgs;
+    all[n_all++] = Choice{GEMM_128_PP16, 1, 128 * 128, (own > arrive ? own : arrive) + 5000};
+  }
   for (int parts = g.forced_parts > 0 ? g.forced_parts : 1; parts <= (g.forced_parts > 0 ? g.forced_parts : 8); parts *= 2) {
     // every part keeps at least 8 K steps, and its partial tiles must fit the scratch allowed
     if (parts > 1 && KT < 8 * parts) break;
@@ -601,7 +617,9 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   bool have = false;
   for (int i = 0; i < n_all; ++i) {
     if (all[i].t > best + best / 12) continue;
-    if (!have || all[i].area > pick.area || (all[i].area == pick.area && all[i].parts < pick.parts)) pick = all[i];
+    if (!have || all[i].area > pick.area || (all[i].area == pick.area && all[i].parts < pick.parts) ||
+        (all[i].area == pick.area && all[i].parts == pick.parts && all[i].t < pick.t))
+      pick = all[i];
     have = true;
   }
   int v = pick.variant;
@@ -635,6 +653,7 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       g.forced != GEMM_SKINNY_DMA)
     v = g.forced;
   if ((v == GEMM_256_PP16 || v == GEMM_256_W4) && !gemm_pp_ok(g)) v = GEMM_256_W8;
+  if (v == GEMM_128_PP16 && !gemm_pp_ok(g)) v = GEMM_128_W8;
   // a forced kernel keeps the split only if it is one of the kernels that can run it
   const bool can_split = v == GEMM_128_K2 || v == GEMM_64X128_K2 || v == GEMM_64_K4 || v == GEMM_128_W8 ||
                          v == GEMM_64X128_W8 || v == GEMM_64_W4;
@@ -654,6 +673,9 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     case GEMM_256_PP16: p.bm = p.bn = 256; p.wm = 2; p.wn = 4;
       p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x4_pp16" : "gemm_nn_256x256x64_w2x4_pp16"; break;
+    case GEMM_128_PP16: p.bm = p.bn = 128; p.wm = 2; p.wn = 4;
+      p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
+      p.name = g.transB ? "gemm_nt_128x128x64_w2x4_pp16" : "gemm_nn_128x128x64_w2x4_pp16"; break;
     case GEMM_256_W4: p.bm = p.bn = 256; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x2_swp" : "gemm_nn_256x256x64_w2x2_swp"; break;
     case GEMM_128_W8: p.bm = p.bn = 128; p.wm = 2; p.wn = 4;
@@ -703,7 +725,8 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_128_K2: return launch_tile_tb<Tag, 128, 128, 64, 2, 4, 2>(g, s);
     case GEMM_64X128_K2: return launch_tile_tb<Tag, 64, 128, 64, 2, 4, 2>(g, s);
     case GEMM_64_K4: return launch_tile_tb<Tag, 64, 64, 64, 2, 2, 4, 3>(g, s);
-    case GEMM_256_PP16: return run_gemm_pp(g, s);
+    case GEMM_256_PP16: return run_gemm_pp(g, 256, s);
+    case GEMM_128_PP16: return run_gemm_pp(g, 128, s);
     case GEMM_256_W4: return run_gemm_w4(g, s);
     case GEMM_SKINNY: return run_gemm_skinny(g, s);
     case GEMM_SKINNY_DMA: return run_gemm_skinny_dma(g, s);

@@ -41,23 +41,17 @@ namespace mlt {
 
 namespace {
 
-constexpr int PP_BM = 256, PP_BN = 256, PP_BK = 64;
+constexpr int PP_BK = 64;
 constexpr int PP_NT = 512;
-constexpr int PP_A_BYTES = PP_BM * PP_BK * 2;            // 32 KB
-constexpr int PP_B_BYTES = PP_BN * PP_BK * 2;            // 32 KB
-constexpr int PP_SLOT = 32768;                           // one operand tile
 constexpr int PP_NSLOT = 5;
-constexpr int PP_SMEM = PP_NSLOT * PP_SLOT;              // 160 KB
-static_assert(PP_A_BYTES == PP_SLOT && PP_B_BYTES == PP_SLOT, "one tile per slot");
-
-typedef const __attribute__((address_space(1))) void* gptr_t;
-
-// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
-constexpr int WAIT_LGKM0 = 0xC07F;       // lgkmcnt(0)
-constexpr int WAIT_VM0_LGKM0 = 0x0070;   // vmcnt(0) lgkmcnt(0)
-constexpr int WAIT_VM0 = 0x0F70;         // vmcnt(0)
-constexpr int WAIT_VM8 = 0x0F78;         // vmcnt(8)
-constexpr int WAIT_VM8_LGKM0 = 0x0078;   // vmcnt(8) lgkmcnt(0)
+// The workgroup tile is BT x BT (BT = 256: one workgroup per CU, the 160 KB ring described above;
+// BT = 128: the same schedule with 64 x 32 per wavefront, 16 KB slots and at most 128 registers,
+// so that two workgroups share a CU and one computes while the other waits at a barrier).
+template <int BT> struct PpTile {
+  static constexpr int SLOT = BT * PP_BK * 2;            // one operand tile: 32 KB / 16 KB
+  static constexpr int SMEM = PP_NSLOT * SLOT;           // 160 KB / 80 KB
+  static constexpr int NL = BT / 32;                     // 1 KB blocks per wavefront and tile: 8 / 4
+};
 
 // Workgroup id -> C tile: bands of 4 tile rows, column by column, so an XCD's 32 resident
 // workgroups form a 4 x 8 block of tiles that shares 4 row panels of A and 8 column panels of B.
@@ -83,34 +77,39 @@ __device__ __forceinline__ auto mfma_ms(V8 a, V8 b, typename std::conditional<MS
 
 }  // namespace
 
-template <typename Tag, bool TRANSB, int MS>
-__global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
+template <typename Tag, bool TRANSB, int MS, int BT>
+__global__ __launch_bounds__(PP_NT, BT == 128 ? 4 : 1) void gemm_pp_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
     int nbn, int nxcd, int epi, const uint16_t* __restrict__ bias) {
   typedef typename Elem<Tag>::vec8 V8;
+  typedef PpTile<BT> T;
+  static_assert(BT == 256 || (BT == 128 && MS == 16), "tile sizes that were built and measured");
+  constexpr int PP_BM = BT, PP_BN = BT, PP_SLOT = T::SLOT, NL = T::NL;
+  constexpr int WTM = BT / 2, WTN = BT / 4;              // per wavefront: 128 x 64 / 64 x 32
+  constexpr int BROW = BT * 2;                           // bytes per k row of the K x N tile
   extern __shared__ __align__(16) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3;               // 2 x 4 wavefronts of 128 x 64
+  const int wm = wave >> 2, wn = wave & 3;               // 2 x 4 wavefronts
   const int grp = wm;                                    // waves 0-3 / 4-7: one of each per SIMD
   int tile_m, tile_n;
   tile_of_block<PP_GROUP_M>(blockIdx.x, nbm, nbn, nxcd, tile_m, tile_n);
   const int m0 = tile_m * PP_BM, n0 = tile_n * PP_BN;
 
-  // ---- global -> LDS assignments. A tile is 32 blocks of 1 KB (64 lanes x 16 bytes). The four
-  // wavefronts of group 1 fill the A tiles, those of group 0 the B tiles, 8 blocks each; lane l
-  // owns the 16-byte slot l of a block.
+  // ---- global -> LDS assignments. A tile is 32 (16) blocks of 1 KB (64 lanes x 16 bytes). The
+  // four wavefronts of group 1 fill the A tiles, those of group 0 the B tiles, NL blocks each;
+  // lane l owns the 16-byte slot l of a block.
   const char* ld_base;                                   // uniform: tile origin at k = 0
   int64_t ld_kstep;                                      // uniform: bytes per K step
-  uint32_t voff[8];
+  uint32_t voff[NL];
   if (grp == 1) {
     ld_base = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
     ld_kstep = PP_BK * 2;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = ((wave & 3) * 8 + i) * 8 + (lane >> 3);   // tile row held by this slot
+    for (int i = 0; i < NL; ++i) {
+      const int r = ((wave & 3) * NL + i) * 8 + (lane >> 3);  // tile row held by this slot
       const int c = (lane & 7) ^ ((r >> 1) & 7);              // k chunk stored in this slot
       const int rr = (m0 + r < M) ? r : (M - 1 - m0);
       voff[i] = (uint32_t)rr * (uint32_t)lda * 2u + (uint32_t)c * 16u;
@@ -119,8 +118,8 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     ld_base = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
     ld_kstep = PP_BK * 2;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = ((wave & 3) * 8 + i) * 8 + (lane >> 3);
+    for (int i = 0; i < NL; ++i) {
+      const int r = ((wave & 3) * NL + i) * 8 + (lane >> 3);
       const int c = (lane & 7) ^ ((r >> 1) & 7);
       const int rr = (n0 + r < N) ? r : (N - 1 - n0);
       voff[i] = (uint32_t)rr * (uint32_t)ldb * 2u + (uint32_t)c * 16u;
@@ -128,22 +127,23 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   } else {
     ld_base = reinterpret_cast<const char*>(B);
     ld_kstep = (int64_t)PP_BK * ldb * 2;
+    constexpr int LPR = BT / 8, RPB = 64 / LPR;             // lanes per k row, k rows per block
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int k = ((wave & 3) * 8 + i) * 2 + (lane >> 5);   // tile k row held by this slot
-      const int q = (lane & 31) ^ swz_kn<MS>(k);              // n chunk stored in this slot
+    for (int i = 0; i < NL; ++i) {
+      const int k = ((wave & 3) * NL + i) * RPB + lane / LPR;  // tile k row held by this slot
+      const int q = (lane % LPR) ^ swz_kn<MS>(k);              // n chunk stored in this slot
       const int col = n0 + q * 8;
       voff[i] = (uint32_t)k * (uint32_t)ldb * 2u + (uint32_t)(col < N ? col : 0) * 2u;
     }
   }
   const int KT = K / PP_BK;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;      // LDS byte address of the buffer
-  // this wavefront's 8 blocks of operand tile t (A_t for group 1, B_t for group 0) into a slot
+  // this wavefront's NL blocks of operand tile t (A_t for group 1, B_t for group 0) into a slot
   auto issue_loads = [&](int t, int slot) {
     const char* gp = ld_base + (int64_t)t * ld_kstep;
-    const uint32_t dst = lds0 + slot * PP_SLOT + (wave & 3) * 8192;
+    const uint32_t dst = lds0 + slot * PP_SLOT + (wave & 3) * (NL * 1024);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) load_lds16(gp, voff[i], dst + i * 1024);
+    for (int i = 0; i < NL; ++i) load_lds16(gp, voff[i], dst + i * 1024);
   };
   // ---- fragment addresses inside a stage (per lane; tile and k slice offsets are immediates)
   // MS = 32: MFMA 32x32x16, 4 k slices of 16 per K step, A tiles of 32 rows, B tiles of 32 columns.
@@ -153,18 +153,18 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   // against 1850 TFLOP/s of 32x32x16 (a register-only MFMA loop; power-limited clocks 2.05 against
   // 1.81 GHz).
   constexpr int NS = MS == 32 ? 4 : 2;                    // k slices per K step
-  constexpr int TA = 128 / MS, TB = 64 / MS;              // A / B tiles per wavefront
+  constexpr int TA = WTM / MS, TB = WTN / MS;             // A / B tiles per wavefront
   const int lq = lane & (MS - 1), h = lane / MS;          // row (column) within a tile, k chunk of the slice
   constexpr int CPS = 64 / MS;                            // 16-byte k chunks per slice (2 or 4)
   int a_off[NS], b_off[4];
   {
-    const int r = wm * 128 + lq;
+    const int r = wm * WTM + lq;
     const int f = (lq >> 1) & 7;
 #pragma unroll
     for (int kk = 0; kk < NS; ++kk) a_off[kk] = r * 128 + (((CPS * kk + h) ^ f) * 16);
   }
   if (TRANSB) {
-    const int r = wn * 64 + lq;
+    const int r = wn * WTN + lq;
     const int f = (lq >> 1) & 7;
 #pragma unroll
     for (int kk = 0; kk < NS; ++kk) b_off[kk] = r * 128 + (((CPS * kk + h) ^ f) * 16);
@@ -175,8 +175,8 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     const int krow = 8 * (g >> 1) + (s >> 2);
     const int q = wn * 8 + 2 * (g & 1) + ((s & 3) >> 1);
     const int x = 4 * (s >> 2);
-    b_off[0] = krow * 512 + ((q ^ x) * 16) + 8 * (s & 1);        // column tile 0
-    b_off[1] = krow * 512 + (((q + 4) ^ x) * 16) + 8 * (s & 1);  // column tile 1
+    b_off[0] = krow * BROW + ((q ^ x) * 16) + 8 * (s & 1);        // column tile 0
+    b_off[1] = krow * BROW + (((q + 4) ^ x) * 16) + 8 * (s & 1);  // column tile 1
     b_off[2] = b_off[3] = 0;
   } else {
     // 16-wide tiles: 16-lane group g serves k slots 8*g.. of the 32-deep slice for all 16 columns;
@@ -185,9 +185,9 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     const int krow = 8 * g + (s >> 2);
     const int x = swz_kn<16>(krow);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int q = wn * 8 + 2 * j + ((s & 3) >> 1);
-      b_off[j] = krow * 512 + ((q ^ x) * 16) + 8 * (s & 1);
+    for (int j = 0; j < TB; ++j) {
+      const int q = wn * (WTN / 8) + 2 * j + ((s & 3) >> 1);
+      b_off[j] = krow * BROW + ((q ^ x) * 16) + 8 * (s & 1);
     }
   }
 
@@ -211,9 +211,9 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
         if (TRANSB) {
           bf[kk][j] = lds_read8<V8>(sb, b_off[kk] + j * MS * 128);
         } else {
-          const int o = b_off[j] + kk * (64 / NS) * 512;
+          const int o = b_off[j] + kk * (64 / NS) * BROW;
           const s16x4 lo = lds_read_tr4(sb, o);
-          const s16x4 hi = lds_read_tr4(sb, o + 4 * 512);
+          const s16x4 hi = lds_read_tr4(sb, o + 4 * BROW);
           bf[kk][j] = join_tr<V8>(lo, hi);
         }
       }
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   // multiplies in phase 2k+1; group 1 does the same one phase later. Operand tile number h
   // (A_k: h = 2k, B_k: h = 2k+1) lives in slot h % 5 and is last read in phase 2k+1.
   //   group 1, memory phase of step k (phase 2k+1): issues A_{k+2} into the slot B_{k-1} left in
-  //     phase 2k-1, then makes sure A_{k+1} (issued one step earlier) has landed: at most the 8
+  //     phase 2k-1, then makes sure A_{k+1} (issued one step earlier) has landed: at most the NL
   //     loads just issued may still be in flight;
   //   group 0, memory phase of step k (phase 2k): issues B_{k+1} into the slot A_{k-1} left in
   //     phase 2k-1, and waits for it at the end of its compute phase (phase 2k+1).
@@ -233,12 +233,12 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   // phase 2k+2) comes after that barrier.
   if (grp == 1) {
     issue_loads(0, 0);
-    if (KT > 1) { issue_loads(1, 2); __builtin_amdgcn_s_waitcnt(WAIT_VM8); }
-    else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+    if (KT > 1) { issue_loads(1, 2); __builtin_amdgcn_s_waitcnt(wait_imm(NL, 15)); }
+    else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
   } else {
     issue_loads(0, 1);
-    if (KT > 1) { issue_loads(1, 3); __builtin_amdgcn_s_waitcnt(WAIT_VM8); }
-    else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+    if (KT > 1) { issue_loads(1, 3); __builtin_amdgcn_s_waitcnt(wait_imm(NL, 15)); }
+    else __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
   }
   MLT_BARRIER();
   if (grp == 1) MLT_BARRIER();
@@ -252,14 +252,14 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
     if (grp == 1) {
       if (k + 2 < KT) {
         issue_loads(k + 2, slot_a + 4 >= PP_NSLOT ? slot_a + 4 - PP_NSLOT : slot_a + 4);
-        __builtin_amdgcn_s_waitcnt(WAIT_VM8_LGKM0);
+        __builtin_amdgcn_s_waitcnt(wait_imm(NL, 0));
       } else {
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0_LGKM0);
+        __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
       }
     } else {
       if (k >= 1 && k + 1 < KT)
         issue_loads(k + 1, slot_a + 3 >= PP_NSLOT ? slot_a + 3 - PP_NSLOT : slot_a + 3);
-      __builtin_amdgcn_s_waitcnt(WAIT_LGKM0);
+      __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
     }
     MLT_BARRIER();
     __builtin_amdgcn_sched_barrier(0);
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
 #pragma unroll
         for (int j = 0; j < TB; ++j) acc[i][j] = mfma_ms<MS>(af[kk][i], bf[kk][j], acc[i][j]);
     __builtin_amdgcn_sched_barrier(0);
-    if (grp == 0) __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+    if (grp == 0) __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
     MLT_BARRIER();
     __builtin_amdgcn_sched_barrier(0);
     slot_a = slot_a + 2 >= PP_NSLOT ? slot_a + 2 - PP_NSLOT : slot_a + 2;
@@ -281,8 +281,8 @@ __global__ __launch_bounds__(PP_NT) void gemm_pp_kernel(
   // ---- epilogue: fp32 -> 16-bit (RNE) and store, or add to the fp32 C; guarded per element
   // accumulator register r of a 32x32 tile is row 8*(r/4) + 4*(l/32) + r%4, of a 16x16 tile row
   // 4*(l/16) + r; the column is the lane's
-  const int row_base = m0 + wm * 128 + 4 * h;
-  const int col_base = n0 + wn * 64 + lq;
+  const int row_base = m0 + wm * WTM + 4 * h;
+  const int col_base = n0 + wn * WTN + lq;
   if constexpr (MS == 16) {
     // Plain 16-bit store with even N and ldc: neighbouring lanes (columns c, c+1 of the same four
     // rows) exchange two of their four values, so that the even lane holds rows 0, 1 and the odd
@@ -333,6 +333,7 @@ bool gemm_pp_ok(const GemmArgs& g) {
   auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   if (!al16(g.A) || !al16(g.B)) return false;
   if (g.K < PP_BK || g.K % PP_BK || g.lda % 8 || g.ldb % 8) return false;
+  if (g.M < 1 || g.N < 1) return false;
   if (!g.transB && g.N % 8) return false;
   const int64_t lim = (int64_t)1 << 30;
   if (256 * g.lda >= lim) return false;
@@ -340,9 +341,10 @@ bool gemm_pp_ok(const GemmArgs& g) {
   return true;
 }
 
-template <typename Tag, bool TRANSB, int MS>
+template <typename Tag, bool TRANSB, int MS, int BT>
 static int launch_pp(const GemmArgs& g, hipStream_t s) {
-  auto kern = gemm_pp_kernel<Tag, TRANSB, MS>;
+  constexpr int PP_BM = BT, PP_BN = BT, PP_SMEM = PpTile<BT>::SMEM;
+  auto kern = gemm_pp_kernel<Tag, TRANSB, MS, BT>;
   static thread_local int configured_dev = -1;          // opt in to > 64 KB LDS once per device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
@@ -363,11 +365,16 @@ static int launch_pp(const GemmArgs& g, hipStream_t s) {
 // Only the 16x16x32 form is instantiated (MS = 16): measured on N(0,1) operands it runs 8-17 %
 // faster than the 32x32x16 form of the same schedule (the chip is power-limited and this MFMA
 // shape moves half as many accumulator registers per flop).
-int run_gemm_pp(const GemmArgs& g, hipStream_t s) {
+int run_gemm_pp(const GemmArgs& g, int tile, hipStream_t s) {
   constexpr int MS = 16;
+  if (tile == 128) {
+    if (g.dtype == MLT_BF16)
+      return g.transB ? launch_pp<bf16_tag, true, MS, 128>(g, s) : launch_pp<bf16_tag, false, MS, 128>(g, s);
+    return g.transB ? launch_pp<f16_tag, true, MS, 128>(g, s) : launch_pp<f16_tag, false, MS, 128>(g, s);
+  }
   if (g.dtype == MLT_BF16)
-    return g.transB ? launch_pp<bf16_tag, true, MS>(g, s) : launch_pp<bf16_tag, false, MS>(g, s);
-  return g.transB ? launch_pp<f16_tag, true, MS>(g, s) : launch_pp<f16_tag, false, MS>(g, s);
+    return g.transB ? launch_pp<bf16_tag, true, MS, 256>(g, s) : launch_pp<bf16_tag, false, MS, 256>(g, s);
+  return g.transB ? launch_pp<f16_tag, true, MS, 256>(g, s) : launch_pp<f16_tag, false, MS, 256>(g, s);
 }
 
 }  // namespace mlt

@@ -57,11 +57,13 @@ def test_exact_tiles(variant, transB):
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("shape", [(520, 776, 320), (512, 768, 256), (100, 40, 64), (257, 264, 128)])
 def test_two_group_kernel(shape, transB, dtype):
-    # the direct-to-LDS two-group kernel (16x16x32 MFMAs): K a multiple of 64, ragged and exact
-    # M/N, one and many K steps
+    # the direct-to-LDS two-group kernel (16x16x32 MFMAs) on both of its tile sizes: K a multiple
+    # of 64, ragged and exact M/N, one and many K steps
     M, N, K = shape
     name, _ = _go(M, N, K, dtype, transB, variant="256pp16", seed=6)
-    assert name.endswith("_pp16")
+    assert name.endswith("256x256x64_w2x4_pp16")
+    name, _ = _go(M, N, K, dtype, transB, variant="128pp16", seed=6)
+    assert name.endswith("128x128x64_w2x4_pp16")
 
 
 @pytest.mark.parametrize("dtype", [BF16, FP16])
@@ -70,8 +72,9 @@ def test_two_group_kernel_store_forms(case, dtype):
     # the 16x16x32 form stores pairs of columns as 32-bit words when N and ldc are even and falls
     # back to element stores otherwise: odd N (B stored N x K), odd and even padded ldc, odd M
     M, N, K, ldc_pad = case
-    name, _ = _go(M, N, K, dtype, True, variant="256pp16", seed=13, ldc_pad=ldc_pad)
-    assert name.endswith("_pp16")
+    for variant in ("256pp16", "128pp16"):
+        name, _ = _go(M, N, K, dtype, True, variant=variant, seed=13, ldc_pad=ldc_pad)
+        assert name.endswith("_pp16")
 
 
 @pytest.mark.parametrize("transB", [False, True])
@@ -258,6 +261,7 @@ def test_padded_leading_dimensions(transB):
 
 
 @pytest.mark.parametrize("variant,shape,transB", [("256pp16", (300, 264, 192), False), ("256pp16", (300, 264, 192), True),
+                                                  ("128pp16", (300, 264, 192), False), ("128pp16", (300, 264, 192), True),
                                                   ("256w4", (300, 264, 192), False),
                                                   ("256w4", (300, 264, 192), True), ("skinnydma", (16, 1100, 1032), True),
                                                   ("skinnydma", (40, 1100, 1032), True), ("skinny", (16, 1100, 1032), True)])
@@ -333,7 +337,7 @@ def test_decode_shapes_streaming_kernels_full_size(shape, suffix):
     assert suffix in name
 
 
-@pytest.mark.parametrize("variant", [None, "256pp16", "128w8", "general"])
+@pytest.mark.parametrize("variant", [None, "256pp16", "128pp16", "128w8", "general"])
 @pytest.mark.parametrize("transB", [False, True])
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 def test_accumulate_into_fp32_c(variant, transB, dtype):
@@ -382,7 +386,7 @@ def test_accumulate_edge_cases():
 
 @pytest.mark.parametrize("act", [0, 1, 2])
 @pytest.mark.parametrize("with_bias", [False, True])
-@pytest.mark.parametrize("variant,shape", [("256pp16", (520, 776, 320)), ("256", (300, 264, 200)),
+@pytest.mark.parametrize("variant,shape", [("256pp16", (520, 776, 320)), ("128pp16", (520, 776, 320)), ("256", (300, 264, 200)),
                                            ("128w8", (260, 392, 136)), ("general", (70, 53, 29)),
                                            (None, (16, 2048, 512))])
 def test_fused_bias_activation(variant, shape, with_bias, act):
@@ -399,7 +403,7 @@ def test_fused_bias_activation(variant, shape, with_bias, act):
         print("   kernel=%s %s" % (name, st), flush=True)
         if with_bias or act:
             assert "skinny" not in name
-        if variant == "256pp16":
+        if variant in ("256pp16", "128pp16"):
             assert name.endswith("_pp16")
 
 
