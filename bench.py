@@ -149,14 +149,15 @@ def cpu_baseline(A, B, Q, K, V, scale):
 
 
 PAGED_SHAPE = (64, 32, 4096, 128, 16)   # sequences, heads, keys per sequence, head dim, block size
+PAGED_SHAPE_FEW = (1, 8, 32768, 128, 16)   # too few (sequence, head) pairs for the chip: keys split over workgroups
 
 
-def paged_decode(binding, ev, dev):
+def paged_decode(binding, ev, dev, shape=PAGED_SHAPE):
     """The paged-attention decode kernel (paper Section 3.2) on a bf16 cache of B x H x S keys in
     shuffled 16-key blocks (N(0,1), torch seed 0, generated on the device): HBM-bound, reported in
     GB/s of algorithmic bytes (K and V cache read once, Q and O) against the 8 TB/s peak."""
     import torch
-    Bp, Hp, Sp, Dp, bs = PAGED_SHAPE
+    Bp, Hp, Sp, Dp, bs = shape
     g = torch.Generator(device=dev)
     g.manual_seed(0)
     nb = Bp * (Sp // bs)
@@ -185,7 +186,7 @@ def paged_decode(binding, ev, dev):
     gbs = nbytes / (ms * 1e-3) / 1e9
     return {"kernel": binding.mlt_last_kernel(), "avg_ms": ms, "GB_per_s": gbs,
             "frac_hbm_peak": gbs / 8000.0, "bytes_per_launch": nbytes,
-            "workload": "B=%d H=%d S=%d D=%d block=%d bf16, shuffled blocks" % PAGED_SHAPE}
+            "workload": "B=%d H=%d S=%d D=%d block=%d bf16, shuffled blocks" % shape}
 
 
 def hbm_ceiling(binding, ev, dev):
@@ -517,10 +518,11 @@ def main():
         return
 
     if args.only == "paged":
-        r = paged_decode(binding, HipEvents(), dev)
+        for shape in (PAGED_SHAPE, PAGED_SHAPE_FEW):
+            r = paged_decode(binding, HipEvents(), dev, shape)
+            print("paged: %s (%s) avg %.4f ms, %.1f GB/s" % (r["kernel"], r["workload"], r["avg_ms"], r["GB_per_s"]))
         if args.copy_calibration:
             copy_calibration()
-        print("paged: %s avg %.4f ms, %.1f GB/s" % (r["kernel"], r["avg_ms"], r["GB_per_s"]))
         return
 
     M, N, Kd = GEMM_MNK
@@ -622,6 +624,7 @@ def main():
     if not args.no_ceiling:
         out["mfma_ceiling"] = mfma_ceiling(binding, ev, A, dev)
         out["paged_decode"] = paged_decode(binding, ev, dev)
+        out["paged_decode_few_pairs"] = paged_decode(binding, ev, dev, PAGED_SHAPE_FEW)
         out["hbm_ceiling"] = hbm_ceiling(binding, ev, dev)
         out["power"] = power_context(binding, A, B, C, Q, K, V, O, scale)
         # second number beside the nominal fraction: against what a register-only loop of the same
