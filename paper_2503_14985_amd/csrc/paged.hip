@@ -203,14 +203,24 @@ __global__ __launch_bounds__(PG_NT) void paged_decode_kernel(
 template <typename Tag, int D>
 __global__ __launch_bounds__(D) void paged_merge_kernel(const float* __restrict__ part,
                                                         uint16_t* __restrict__ O, int nsplit) {
+  // the ranges' maxima and sums go through LDS (one load each, all in flight together), the
+  // output slices are read with eight loads in flight per thread: a plain loop over the ranges
+  // would wait for one memory round trip after the other (measured 16 us for 32 ranges)
+  __shared__ float sm[64], sl[64];
   const int bh = blockIdx.x, tid = threadIdx.x;
   const float* p = part + (int64_t)bh * nsplit * (2 + D);
-  float M = p[0];
-  for (int s = 1; s < nsplit; ++s) M = __builtin_fmaxf(M, p[s * (2 + D)]);
+  if (tid < nsplit) {
+    sm[tid] = p[tid * (2 + D)];
+    sl[tid] = p[tid * (2 + D) + 1];
+  }
+  __syncthreads();
+  float M = sm[0];
+  for (int s = 1; s < nsplit; ++s) M = __builtin_fmaxf(M, sm[s]);
   float L = 0.f, acc = 0.f;
+#pragma unroll 8
   for (int s = 0; s < nsplit; ++s) {
-    const float wgt = __builtin_amdgcn_exp2f(p[s * (2 + D)] - M);   // empty ranges: exp2(-inf) = 0
-    L += p[s * (2 + D) + 1] * wgt;
+    const float wgt = __builtin_amdgcn_exp2f(sm[s] - M);           // empty ranges: exp2(-inf) = 0
+    L += sl[s] * wgt;
     acc += p[s * (2 + D) + 2 + tid] * wgt;
   }
   O[(int64_t)bh * D + tid] = Elem<Tag>::from_f32(acc / L);
