@@ -84,8 +84,9 @@ def test_side_stream_matches_default_stream():
 
 
 def test_captured_step_replays_to_the_eager_result():
-    """Capture one step into a HIP graph (the entry points allocate nothing and launch only
-    kernels), replay it several times with eager work and synchronisations in between and with new
+    """Capture one step into a HIP graph (on these shapes the entry points launch only kernels and
+    need no scratch of the library's own; the captured form of a call that does is
+    mlt_gemm_noalloc, tested with its own file), replay it several times with eager work and synchronisations in between and with new
     input contents, and compare every replay with the eager result on the same contents."""
     from paper_2503_14985_amd import binding
     dev = torch.device("cuda:0")

@@ -57,3 +57,36 @@ def test_no_alloc_entry_point_matches_the_allocating_one():
         assert torch.all(got == 7.0)
     finally:
         binding.mlt_diag_force_k_parts(0)
+
+
+def test_no_alloc_entry_point_inside_a_captured_graph():
+    """What the entry point is for: a K-split GEMM captured into a HIP graph (on the capture stream
+    the allocating entry point would have to hipMalloc its scratch in the middle of the capture).
+    Replayed several times, with eager work in between and new input contents, against the eager
+    result of mlt_gemm on the same contents."""
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    binding.mlt_diag_force_variant(gemm="auto")
+    binding.mlt_diag_force_k_parts(0)
+    M, N, K = 64, 2048, 64 * 160
+    A, B, tA, tB = _pair(M, N, K, 80, dev)
+    _, _, oA, oB = _pair(M, N, K, 81, dev)
+    eager = binding.mlt_gemm(tA, tB, transB=True)
+    assert "splitk" in binding.mlt_last_kernel()
+    static = torch.empty_like(eager)
+    binding.mlt_gemm_noalloc(tA, tB, static, transB=True)      # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.mlt_gemm_noalloc(tA, tB, static, transB=True)
+    for rep in range(4):
+        if rep == 2:
+            tA.copy_(oA)
+            tB.copy_(oB)
+            eager = binding.mlt_gemm(tA, tB, transB=True)
+        static.fill_(0)
+        graph.replay()
+        other = binding.mlt_gemm(oA, oB, transB=True)           # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(static.view(torch.int16), eager.view(torch.int16)), "replay %d" % rep
+        del other
