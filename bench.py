@@ -471,7 +471,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle timing (used when profiling)")
     ap.add_argument("--only", choices=["gemm", "mha", "paged"], default=None,
@@ -618,7 +618,14 @@ def main():
                                "one of each per step"},
         "gemm": kernel_line(names[0], gemm_ms, gemm_tf, f_gemm, t_gemm),
         "mha": dict(kernel_line(names[1], mha_ms, mha_tf, f_mha, t_mha),
-                    flop_convention="4*B*H*Sq*Sk*D"),
+                    flop_convention="4*B*H*Sq*Sk*D",
+                    # the second bound of this kernel: the softmax on the vector ALU. Per 64-key tile
+                    # a wavefront (32 query rows) issues 32 v_exp_f32 (8.3 clk each, measured) and
+                    # about 113 other vector instructions (5.1 clk) for 4*D*32*64 flop of MFMA work
+                    valu_bound={"tflops": 1024 * 2.4e9 / (32 * 8.3 + 113 * 5.1) * 4 * D * 32 * 64 / 1e12,
+                                "note": "1024 SIMDs x 2.4 GHz / (vector ALU clocks per key tile and "
+                                        "wavefront) x MFMA flop per key tile and wavefront; above the "
+                                        "MFMA peak for D = 128, below it (1.53 PFLOP/s) for D = 64"}),
         "roofline": roofline,
     }
     if not args.no_ceiling:
