@@ -555,11 +555,11 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   DeviceInfo di;
   const int64_t NCU = device_info(di) && di.ncu > 0 ? di.ncu : 256;
   const int64_t KT = (g.K + 63) / 64;
-  auto cost = [&](int64_t bm, int64_t bn, int64_t t_step, int parts) {
+  auto cost = [&](int64_t bm, int64_t bn, int64_t t_step, int64_t fixed, int parts) {
     const int64_t wgs = ((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * parts;
     const int64_t rounds = (wgs + NCU - 1) / NCU;
     const int64_t steps = (KT + parts - 1) / parts;
-    const int64_t compute = rounds * steps * t_step;
+    const int64_t compute = rounds * (steps * t_step + fixed);
     // operand arrival: both operands once at 5.2 TB/s, which about 0.6 workgroups per CU already
     // draw (measured 37 GB/s per streaming workgroup: 64 of them 2.4 TB/s, 128 4.2, 224 5.7);
     // beyond one workgroup per CU the last round's idle CUs count (448 workgroups take the time
@@ -573,10 +573,12 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   // parts (a larger tile re-reads its operands from L2 less often, which the estimate leaves out:
   // 64 x 8192 x 28672 measured 90 us on 64x128 tiles in four parts, 100 us on 64x64 tiles in two).
   const bool pp = gemm_pp_ok(g);
-  struct Cand { int variant; int bm, bn; int64_t t; };
-  const Cand big = {pp ? GEMM_256_PP16 : GEMM_256_W8, 256, 256, pp ? 1170 : 1800};
-  const Cand split[] = {{GEMM_128_K2, 128, 128, 575}, {GEMM_64X128_K2, 64, 128, 370}, {GEMM_64_K4, 64, 64, 220}};
-  const Cand whole[] = {{GEMM_128_W8, 128, 128, 600}, {GEMM_64X128_W8, 64, 128, 410}, {GEMM_64_W4, 64, 64, 350}};
+  // t: ns per K step of 64; fixed: ns per round before the first and after the last step, where a
+  // fit over K gave one (2048 x 2048 x K on the split 128 x 128 kernel: 0.56 us per step + 2 us)
+  struct Cand { int variant; int bm, bn; int64_t t, fixed; };
+  const Cand big = {pp ? GEMM_256_PP16 : GEMM_256_W8, 256, 256, pp ? 1170 : 1800, 0};
+  const Cand split[] = {{GEMM_128_K2, 128, 128, 560, 2000}, {GEMM_64X128_K2, 64, 128, 370, 0}, {GEMM_64_K4, 64, 64, 220, 0}};
+  const Cand whole[] = {{GEMM_128_W8, 128, 128, 600, 0}, {GEMM_64X128_W8, 64, 128, 410, 0}, {GEMM_64_W4, 64, 64, 350, 0}};
   struct Choice { int variant, parts, area; int64_t t; };
   Choice all[20];
   int n_all = 0;
@@ -584,22 +586,31 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   auto fits = [&](int bm, int bn) {
     return !(bm > 64 && bm > (g.M + 63) / 64 * 64) && !(bn > 64 && bn > (g.N + 63) / 64 * 64);
   };
-  if (g.forced_parts <= 1 && fits(256, 256)) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 1)};
-  // The two-group kernel on 128 x 128 tiles (two workgroups per CU, no K split across workgroups).
-  // Measured per K step and tile: 0.47 us with a second workgroup on the CU, 0.52 us alone, and
-  // about 5 us more than the register-staged kernels before the first and after the last step.
-  // 2048 x 4096 x 4096 (512 tiles): 64 us against 73 on 128 big tiles and 86 on the K-split
-  // 128 x 128 kernel; 1024 x 8192 x 8192: 121 against 134 and 161; with one tile per CU it wins
-  // from about 128 K steps on (512 x 8192 x 8192: 76 against 82), ties at 64 (1024 x 4096 x 4096:
-  // 42.8 against 42.5; 256 x 14336 x 4096: 43.9 against 40.8) and loses to the shorter start
-  // below (2048^3: 27.6 against 25.9).
+  if (g.forced_parts <= 1 && fits(256, 256)) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 0, 1)};
+  // The two-group kernel on 128 x 128 tiles, no K split across workgroups, in its two forms (fits
+  // over K at 256 and 512 tiles, kernel time without the call):
+  //   K steps of 64, two workgroups per CU: 0.84 us per step for a pair of tiles + 1.9 us per pair,
+  //     0.52 us + 4 us for a tile alone on its CU;
+  //   K steps of 128, one workgroup per CU: 0.436 us per 64 of K + 4.3 us per round.
+  // One tile per CU: the 128-deep form (1024 x 4096 x 4096: 35.4 us against 40.8 on the register-
+  // staged split kernel and 43.3 on the 64-deep form, hipBLASLt 36.6; 2048^3: 22.9 against 25.5,
+  // hipBLASLt 25.3; 512 x 8192 x 8192: 65.7 against 76.4, hipBLASLt 64.1). Two tiles per CU: the
+  // 64-deep form, whose workgroups hide each other's start and end (2048 x 4096 x 4096: 60.0
+  // against 69.6 us, 82 on the split kernel, 73 on 128 big tiles; 1024 x 8192 x 8192: 114 against
+  // 132, 153 and 134).
   if (pp && g.forced_parts <= 1 && fits(128, 128)) {
     const int64_t wgs = ((g.M + 127) / 128) * ((g.N + 127) / 128);
-    const int64_t own = wgs <= NCU ? KT * 518 : ((wgs + NCU - 1) / NCU) * KT * 470;
     const int64_t base = (g.M + g.N) * g.K * 2 / 5200;
     const int64_t need = 6 * NCU / 10;
     const int64_t arrive = wgs >= need ? base : base * need / wgs;
-    all[n_all++] = Choice{GEMM_128_PP16, 1, 128 * 128, (own > arrive ? own : arrive) + 5000};
+    const int64_t pairs = wgs / (2 * NCU), rem = wgs - pairs * 2 * NCU;
+    const int64_t own64 = pairs * (KT * 840 + 1900) +
+                          (rem > NCU ? KT * 840 + 1900 : rem > 0 ? KT * 519 + 4000 : 0);
+    all[n_all++] = Choice{GEMM_128_PP16, 1, 128 * 128, own64 > arrive ? own64 : arrive};
+    if (g.K % 128 == 0) {
+      const int64_t own128 = ((wgs + NCU - 1) / NCU) * (KT * 436 + 4300);
+      all[n_all++] = Choice{GEMM_128_PP16_K128, 1, 128 * 128, own128 > arrive ? own128 : arrive};
+    }
   }
   for (int parts = g.forced_parts > 0 ? g.forced_parts : 1; parts <= (g.forced_parts > 0 ? g.forced_parts : 8); parts *= 2) {
     // every part keeps at least 8 K steps, and its partial tiles must fit the scratch allowed
@@ -607,10 +618,10 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     if (parts > 1 && g.scratch_limit >= 0 && (int64_t)parts * g.M * g.N * 4 > g.scratch_limit) break;
     for (const auto& c : KT / parts >= 8 ? split : whole) {
       if (!fits(c.bm, c.bn)) continue;
-      all[n_all++] = Choice{c.variant, parts, c.bm * c.bn, cost(c.bm, c.bn, c.t, parts)};
+      all[n_all++] = Choice{c.variant, parts, c.bm * c.bn, cost(c.bm, c.bn, c.t, c.fixed, parts)};
     }
   }
-  if (n_all == 0) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 1)};
+  if (n_all == 0) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 0, 1)};
   int64_t best = all[0].t;
   for (int i = 1; i < n_all; ++i) best = all[i].t < best ? all[i].t : best;
   Choice pick = all[0];
@@ -653,6 +664,7 @@ GemmPlan plan_gemm(const GemmArgs& g) {
       g.forced != GEMM_SKINNY_DMA)
     v = g.forced;
   if ((v == GEMM_256_PP16 || v == GEMM_256_W4) && !gemm_pp_ok(g)) v = GEMM_256_W8;
+  if (v == GEMM_128_PP16_K128 && (!gemm_pp_ok(g) || g.K % 128)) v = GEMM_128_PP16;
   if (v == GEMM_128_PP16 && !gemm_pp_ok(g)) v = GEMM_128_W8;
   // a forced kernel keeps the split only if it is one of the kernels that can run it
   const bool can_split = v == GEMM_128_K2 || v == GEMM_64X128_K2 || v == GEMM_64_K4 || v == GEMM_128_W8 ||
@@ -676,6 +688,9 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     case GEMM_128_PP16: p.bm = p.bn = 128; p.wm = 2; p.wn = 4;
       p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
       p.name = g.transB ? "gemm_nt_128x128x64_w2x4_pp16" : "gemm_nn_128x128x64_w2x4_pp16"; break;
+    case GEMM_128_PP16_K128: p.bm = p.bn = 128; p.bk = 128; p.wm = 2; p.wn = 4;
+      p.mfma_m = 16; p.mfma_n = 16; p.mfma_k = 32;
+      p.name = g.transB ? "gemm_nt_128x128x128_w2x4_pp16" : "gemm_nn_128x128x128_w2x4_pp16"; break;
     case GEMM_256_W4: p.bm = p.bn = 256; p.wm = 2; p.wn = 2;
       p.name = g.transB ? "gemm_nt_256x256x64_w2x2_swp" : "gemm_nn_256x256x64_w2x2_swp"; break;
     case GEMM_128_W8: p.bm = p.bn = 128; p.wm = 2; p.wn = 4;
@@ -725,8 +740,9 @@ static int run_gemm_t(const GemmArgs& g, const GemmPlan& p, hipStream_t s) {
     case GEMM_128_K2: return launch_tile_tb<Tag, 128, 128, 64, 2, 4, 2>(g, s);
     case GEMM_64X128_K2: return launch_tile_tb<Tag, 64, 128, 64, 2, 4, 2>(g, s);
     case GEMM_64_K4: return launch_tile_tb<Tag, 64, 64, 64, 2, 2, 4, 3>(g, s);
-    case GEMM_256_PP16: return run_gemm_pp(g, 256, s);
-    case GEMM_128_PP16: return run_gemm_pp(g, 128, s);
+    case GEMM_256_PP16: return run_gemm_pp(g, 256, 64, s);
+    case GEMM_128_PP16: return run_gemm_pp(g, 128, 64, s);
+    case GEMM_128_PP16_K128: return run_gemm_pp(g, 128, 128, s);
     case GEMM_256_W4: return run_gemm_w4(g, s);
     case GEMM_SKINNY: return run_gemm_skinny(g, s);
     case GEMM_SKINNY_DMA: return run_gemm_skinny_dma(g, s);

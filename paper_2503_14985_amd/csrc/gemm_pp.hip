@@ -41,16 +41,23 @@ namespace mlt {
 
 namespace {
 
-constexpr int PP_BK = 64;
 constexpr int PP_NT = 512;
 constexpr int PP_NSLOT = 5;
 // The workgroup tile is BT x BT (BT = 256: one workgroup per CU, the 160 KB ring described above;
 // BT = 128: the same schedule with 64 x 32 per wavefront, 16 KB slots and at most 128 registers,
 // so that two workgroups share a CU and one computes while the other waits at a barrier).
-template <int BT> struct PpTile {
-  static constexpr int SLOT = BT * PP_BK * 2;            // one operand tile: 32 KB / 16 KB
-  static constexpr int SMEM = PP_NSLOT * SLOT;           // 160 KB / 80 KB
-  static constexpr int NL = BT / 32;                     // 1 KB blocks per wavefront and tile: 8 / 4
+// BK is the K step: 64, or 128 for BT = 128 (32 KB slots again, one workgroup per CU, phases of
+// twice the length: with 64 x 32 per wavefront a compute phase of one 64-deep step is only 256
+// clocks of MFMA, and the fixed cost of a phase change then costs as much as the phase).
+template <int BT, int BK> struct PpTile {
+  static constexpr int SLOT = BT * BK * 2;               // one operand tile
+  static constexpr int SMEM = PP_NSLOT * SLOT;
+  static constexpr int NL = SLOT / 1024 / 4;             // 1 KB blocks per wavefront and tile
+  static constexpr int AROW = BK * 2;                    // bytes per row of the A (or N x K) tile
+  static constexpr int CPR = BK / 8;                     // 16-byte k chunks per row: 8 or 16
+  // chunk c of row r sits in slot c ^ swz(r): 16 consecutive rows at one chunk must fall in 16
+  // distinct 16-byte bank groups of the 256-byte bank cycle
+  static __device__ __forceinline__ int swz(int r) { return BK == 64 ? (r >> 1) & 7 : r & 15; }
 };
 
 // Workgroup id -> C tile: bands of 4 tile rows, column by column, so an XCD's 32 resident
@@ -77,15 +84,17 @@ __device__ __forceinline__ auto mfma_ms(V8 a, V8 b, typename std::conditional<MS
 
 }  // namespace
 
-template <typename Tag, bool TRANSB, int MS, int BT>
-__global__ __launch_bounds__(PP_NT, BT == 128 ? 4 : 1) void gemm_pp_kernel(
+template <typename Tag, bool TRANSB, int MS, int BT, int BK>
+__global__ __launch_bounds__(PP_NT, (BT == 128 && BK == 64) ? 4 : 1) void gemm_pp_kernel(
     int M, int N, int K, const uint16_t* __restrict__ A, int64_t lda,
     const uint16_t* __restrict__ B, int64_t ldb, uint16_t* __restrict__ C, int64_t ldc, int nbm,
     int nbn, int nxcd, int epi, const uint16_t* __restrict__ bias) {
   typedef typename Elem<Tag>::vec8 V8;
-  typedef PpTile<BT> T;
-  static_assert(BT == 256 || (BT == 128 && MS == 16), "tile sizes that were built and measured");
-  constexpr int PP_BM = BT, PP_BN = BT, PP_SLOT = T::SLOT, NL = T::NL;
+  typedef PpTile<BT, BK> T;
+  static_assert((BT == 256 && BK == 64) || (BT == 128 && MS == 16 && (BK == 64 || BK == 128)),
+                "tile sizes that were built and measured");
+  constexpr int PP_BM = BT, PP_BN = BT, PP_SLOT = T::SLOT, NL = T::NL, PP_BK = BK;
+  constexpr int AROW = T::AROW, CPR = T::CPR, RPBA = 64 / CPR;   // A tile: row bytes, chunks per row, rows per 1 KB block
   constexpr int WTM = BT / 2, WTN = BT / 4;              // per wavefront: 128 x 64 / 64 x 32
   constexpr int BROW = BT * 2;                           // bytes per k row of the K x N tile
   extern __shared__ __align__(16) char smem[];
@@ -109,8 +118,8 @@ __global__ __launch_bounds__(PP_NT, BT == 128 ? 4 : 1) void gemm_pp_kernel(
     ld_kstep = PP_BK * 2;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      const int r = ((wave & 3) * NL + i) * 8 + (lane >> 3);  // tile row held by this slot
-      const int c = (lane & 7) ^ ((r >> 1) & 7);              // k chunk stored in this slot
+      const int r = ((wave & 3) * NL + i) * RPBA + lane / CPR;  // tile row held by this slot
+      const int c = (lane % CPR) ^ T::swz(r);                   // k chunk stored in this slot
       const int rr = (m0 + r < M) ? r : (M - 1 - m0);
       voff[i] = (uint32_t)rr * (uint32_t)lda * 2u + (uint32_t)c * 16u;
     }
@@ -119,8 +128,8 @@ __global__ __launch_bounds__(PP_NT, BT == 128 ? 4 : 1) void gemm_pp_kernel(
     ld_kstep = PP_BK * 2;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      const int r = ((wave & 3) * NL + i) * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      const int r = ((wave & 3) * NL + i) * RPBA + lane / CPR;
+      const int c = (lane % CPR) ^ T::swz(r);
       const int rr = (n0 + r < N) ? r : (N - 1 - n0);
       voff[i] = (uint32_t)rr * (uint32_t)ldb * 2u + (uint32_t)c * 16u;
     }
@@ -152,22 +161,22 @@ __global__ __launch_bounds__(PP_NT, BT == 128 ? 4 : 1) void gemm_pp_kernel(
   // registers per flop, and measured on N(0,1) operands the chip sustains 2100 TFLOP/s of it
   // against 1850 TFLOP/s of 32x32x16 (a register-only MFMA loop; power-limited clocks 2.05 against
   // 1.81 GHz).
-  constexpr int NS = MS == 32 ? 4 : 2;                    // k slices per K step
+  constexpr int NS = BK / (MS == 32 ? 16 : 32);           // k slices per K step
   constexpr int TA = WTM / MS, TB = WTN / MS;             // A / B tiles per wavefront
   const int lq = lane & (MS - 1), h = lane / MS;          // row (column) within a tile, k chunk of the slice
   constexpr int CPS = 64 / MS;                            // 16-byte k chunks per slice (2 or 4)
   int a_off[NS], b_off[4];
   {
     const int r = wm * WTM + lq;
-    const int f = (lq >> 1) & 7;
+    const int f = T::swz(lq);
 #pragma unroll
-    for (int kk = 0; kk < NS; ++kk) a_off[kk] = r * 128 + (((CPS * kk + h) ^ f) * 16);
+    for (int kk = 0; kk < NS; ++kk) a_off[kk] = r * AROW + (((CPS * kk + h) ^ f) * 16);
   }
   if (TRANSB) {
     const int r = wn * WTN + lq;
-    const int f = (lq >> 1) & 7;
+    const int f = T::swz(lq);
 #pragma unroll
-    for (int kk = 0; kk < NS; ++kk) b_off[kk] = r * 128 + (((CPS * kk + h) ^ f) * 16);
+    for (int kk = 0; kk < NS; ++kk) b_off[kk] = r * AROW + (((CPS * kk + h) ^ f) * 16);
   } else if (MS == 32) {
     // transposing read: 16-lane group g serves columns 16*(g%2).. of the 32-wide tile and k slots
     // 8*(g/2)..; lane s of the group addresses k row s/4 (+4 for the second read), columns 4*(s%4)..
@@ -205,13 +214,13 @@ __global__ __launch_bounds__(PP_NT, BT == 128 ? 4 : 1) void gemm_pp_kernel(
 #pragma unroll
     for (int kk = 0; kk < NS; ++kk) {
 #pragma unroll
-      for (int i = 0; i < TA; ++i) af[kk][i] = lds_read8<V8>(sa, a_off[kk] + i * MS * 128);
+      for (int i = 0; i < TA; ++i) af[kk][i] = lds_read8<V8>(sa, a_off[kk] + i * MS * AROW);
 #pragma unroll
       for (int j = 0; j < TB; ++j) {
         if (TRANSB) {
-          bf[kk][j] = lds_read8<V8>(sb, b_off[kk] + j * MS * 128);
+          bf[kk][j] = lds_read8<V8>(sb, b_off[kk] + j * MS * AROW);
         } else {
-          const int o = b_off[j] + kk * (64 / NS) * BROW;
+          const int o = b_off[j] + kk * (BK / NS) * BROW;
           const s16x4 lo = lds_read_tr4(sb, o);
           const s16x4 hi = lds_read_tr4(sb, o + 4 * BROW);
           bf[kk][j] = join_tr<V8>(lo, hi);
@@ -332,19 +341,20 @@ __global__ __launch_bounds__(PP_NT, BT == 128 ? 4 : 1) void gemm_pp_kernel(
 bool gemm_pp_ok(const GemmArgs& g) {
   auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   if (!al16(g.A) || !al16(g.B)) return false;
-  if (g.K < PP_BK || g.K % PP_BK || g.lda % 8 || g.ldb % 8) return false;
+  if (g.K < 64 || g.K % 64 || g.lda % 8 || g.ldb % 8) return false;
   if (g.M < 1 || g.N < 1) return false;
   if (!g.transB && g.N % 8) return false;
   const int64_t lim = (int64_t)1 << 30;
   if (256 * g.lda >= lim) return false;
-  if (g.transB ? 256 * g.ldb >= lim : 64 * g.ldb + g.N >= lim) return false;
+  if (g.transB ? 256 * g.ldb >= lim : 128 * g.ldb + g.N >= lim) return false;
   return true;
 }
 
-template <typename Tag, bool TRANSB, int MS, int BT>
+template <typename Tag, bool TRANSB, int MS, int BT, int BK>
 static int launch_pp(const GemmArgs& g, hipStream_t s) {
-  constexpr int PP_BM = BT, PP_BN = BT, PP_SMEM = PpTile<BT>::SMEM;
-  auto kern = gemm_pp_kernel<Tag, TRANSB, MS, BT>;
+  constexpr int PP_BM = BT, PP_BN = BT, PP_SMEM = PpTile<BT, BK>::SMEM;
+  if (g.K % BK) return MLT_ERR_UNSUPPORTED;
+  auto kern = gemm_pp_kernel<Tag, TRANSB, MS, BT, BK>;
   static thread_local int configured_dev = -1;          // opt in to > 64 KB LDS once per device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return MLT_ERR_DEVICE;
@@ -365,16 +375,17 @@ static int launch_pp(const GemmArgs& g, hipStream_t s) {
 // Only the 16x16x32 form is instantiated (MS = 16): measured on N(0,1) operands it runs 8-17 %
 // faster than the 32x32x16 form of the same schedule (the chip is power-limited and this MFMA
 // shape moves half as many accumulator registers per flop).
-int run_gemm_pp(const GemmArgs& g, int tile, hipStream_t s) {
+template <int BT, int BK>
+static int run_pp_t(const GemmArgs& g, hipStream_t s) {
   constexpr int MS = 16;
-  if (tile == 128) {
-    if (g.dtype == MLT_BF16)
-      return g.transB ? launch_pp<bf16_tag, true, MS, 128>(g, s) : launch_pp<bf16_tag, false, MS, 128>(g, s);
-    return g.transB ? launch_pp<f16_tag, true, MS, 128>(g, s) : launch_pp<f16_tag, false, MS, 128>(g, s);
-  }
   if (g.dtype == MLT_BF16)
-    return g.transB ? launch_pp<bf16_tag, true, MS, 256>(g, s) : launch_pp<bf16_tag, false, MS, 256>(g, s);
-  return g.transB ? launch_pp<f16_tag, true, MS, 256>(g, s) : launch_pp<f16_tag, false, MS, 256>(g, s);
+    return g.transB ? launch_pp<bf16_tag, true, MS, BT, BK>(g, s) : launch_pp<bf16_tag, false, MS, BT, BK>(g, s);
+  return g.transB ? launch_pp<f16_tag, true, MS, BT, BK>(g, s) : launch_pp<f16_tag, false, MS, BT, BK>(g, s);
+}
+
+int run_gemm_pp(const GemmArgs& g, int tile, int kstep, hipStream_t s) {
+  if (tile == 128) return kstep == 128 ? run_pp_t<128, 128>(g, s) : run_pp_t<128, 64>(g, s);
+  return run_pp_t<256, 64>(g, s);
 }
 
 }  // namespace mlt

@@ -29,7 +29,7 @@ void note_gemm_kernel(const GemmPlan& p) {
 
 struct VariantName { const char* name; int id; };
 const VariantName kGemmVariants[] = {
-    {"general", GEMM_GENERAL}, {"256", GEMM_256}, {"256w8", GEMM_256_W8}, {"256pp16", GEMM_256_PP16}, {"128pp16", GEMM_128_PP16},
+    {"general", GEMM_GENERAL}, {"256", GEMM_256}, {"256w8", GEMM_256_W8}, {"256pp16", GEMM_256_PP16}, {"128pp16", GEMM_128_PP16}, {"128pp16k128", GEMM_128_PP16_K128},
     {"256w4", GEMM_256_W4}, {"256w8x1", GEMM_256_W8X1}, {"256w1x8", GEMM_256_W1X8},
     {"128w8", GEMM_128_W8}, {"64x128", GEMM_64X128_W8}, {"64", GEMM_64_W4}, {"128k2", GEMM_128_K2},
     {"64x128k2", GEMM_64X128_K2}, {"64k4", GEMM_64_K4}, {"skinny", GEMM_SKINNY},

@@ -23,6 +23,7 @@ enum GemmVariant {
   GEMM_64X128_K2 = 18, // 64x128x64, 2 groups of 8 wavefronts
   GEMM_64_K4 = 19,    // 64x64x64, 4 groups of 4 wavefronts (3 when B is K x N), each group its share of the K steps
   GEMM_128_PP16 = 20, // 128x128x64, 8 wavefronts (2x4) of 64x32, two-group schedule, direct-to-LDS loads, two workgroups per CU
+  GEMM_128_PP16_K128 = 21, // the same tile with K steps of 128 (one workgroup per CU, phases of twice the length)
   GEMM_NUM_VARIANTS
 };
 
@@ -64,7 +65,7 @@ float* static_scratch_of_current_device();
 GemmPlan plan_gemm(const GemmArgs& g);
 int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s);
 bool gemm_pp_ok(const GemmArgs& g);            // gemm_pp.hip: can the two-group kernel take this problem?
-int run_gemm_pp(const GemmArgs& g, int tile, hipStream_t s);   // tile: 256 or 128
+int run_gemm_pp(const GemmArgs& g, int tile, int kstep, hipStream_t s);   // tile: 256 or 128; K step 64 or (tile 128 only) 128
 int run_gemm_w4(const GemmArgs& g, hipStream_t s);   // gemm_w4.hip; same operand requirements (gemm_pp_ok)
 bool gemm_skinny_ok(const GemmArgs& g);        // gemm_skinny.hip
 int run_gemm_skinny(const GemmArgs& g, hipStream_t s);

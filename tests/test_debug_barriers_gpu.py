@@ -40,6 +40,8 @@ GEMM_CASES = [
     (1000, 1000, 4096, True, "auto", None),       # the same, B stored N x K, ragged edge tiles
     (1000, 1000, 2048, False, "128pp16", None),   # the two-group kernel on 128 x 128 tiles, two workgroups per CU
     (1000, 1000, 2048, True, "128pp16", None),
+    (1000, 1000, 2048, False, "128pp16k128", None),   # the same tile with K steps of 128
+    (1000, 1000, 2048, True, "128pp16k128", None),
     (1024, 1024, 1024, False, "auto", 3),         # square hint: the 4-wavefront pipelined kernel
     (1024, 1024, 1024, True, "auto", 3),
     (300, 520, 1000, False, "auto", None),        # register-staged tile kernels

@@ -66,6 +66,21 @@ def test_two_group_kernel(shape, transB, dtype):
     assert name.endswith("128x128x64_w2x4_pp16")
 
 
+@pytest.mark.parametrize("transB", [False, True])
+@pytest.mark.parametrize("dtype", [BF16, FP16])
+@pytest.mark.parametrize("shape", [(520, 776, 384), (512, 768, 128), (100, 40, 256), (257, 264, 1280), (300, 263, 640)])
+def test_two_group_kernel_k_steps_of_128(shape, transB, dtype):
+    # the 128 x 128 tile with K steps of 128: one, few and many steps, ragged M / N, odd N with B
+    # stored N x K; a K that is a multiple of 64 only falls back to the 64-deep form
+    M, N, K = shape
+    if not transB and N % 8:
+        N += 8 - N % 8
+    name, _ = _go(M, N, K, dtype, transB, variant="128pp16k128", seed=16)
+    assert name.endswith("128x128x128_w2x4_pp16")
+    name, _ = _go(M, N, K + 64, dtype, transB, variant="128pp16k128", seed=16)
+    assert name.endswith("128x128x64_w2x4_pp16")
+
+
 @pytest.mark.parametrize("dtype", [BF16, FP16])
 @pytest.mark.parametrize("case", [(300, 263, 128, 0), (259, 520, 192, 1), (259, 520, 192, 3), (513, 262, 64, 2)])
 def test_two_group_kernel_store_forms(case, dtype):
@@ -222,15 +237,16 @@ def test_k_split_inside_the_workgroup(variant, transB, K):
         assert "_k" in name
 
 
-@pytest.mark.parametrize("shape,tile", [((1024, 1024, 1024), "64x64x64_w2x2_k4"), ((2048, 2048, 2048), "128x128x64_w2x4_k2"),
+@pytest.mark.parametrize("shape,tile", [((1024, 1024, 1024), "64x64x64_w2x2_k4"), ((2048, 2048, 2048), "128x128x128_w2x4_pp16"),
                                         ((3072, 3072, 3072), "256x256x64_w2x4_pp16"),
                                         ((512, 8192, 1024), "128x128x64_w2x4_k2"), ((512, 4096, 1024), "64x128x64_w2x4_k2"),
                                         ((256, 4096, 2048), "64x64x64_w2x2_k4"), ((2048, 2048, 2048 + 8), "128x128x64_w2x4_k2"),
                                         ((4096, 4096, 512), "256x256x64_w2x4_pp16"), ((1024, 1024, 256), "64x64x64_w2x2"),
                                         ((2048, 2048, 448), "128x128x64_w2x4")])
 def test_tile_size_routing(shape, tile):
-    """The workgroup tile is the one with the least time per K step over the whole grid: the
-    256 x 256 two-group kernel once its tiles cover enough of the chip, 128 x 128, 64 x 128 or
+    """The workgroup tile is the one with the least estimated time over the whole grid: the
+    256 x 256 two-group kernel once its tiles cover enough of the chip, 128 x 128 (two-group with
+    K steps of 128 when one tile per CU runs long enough, register-staged otherwise), 64 x 128 or
     64 x 64 below that; sampled parity at the real size either way."""
     M, N, K = shape
     name, _ = _go(M, N, K, BF16, False, seed=21)
@@ -262,6 +278,7 @@ def test_padded_leading_dimensions(transB):
 
 @pytest.mark.parametrize("variant,shape,transB", [("256pp16", (300, 264, 192), False), ("256pp16", (300, 264, 192), True),
                                                   ("128pp16", (300, 264, 192), False), ("128pp16", (300, 264, 192), True),
+                                                  ("128pp16k128", (300, 264, 256), False), ("128pp16k128", (300, 264, 256), True),
                                                   ("256w4", (300, 264, 192), False),
                                                   ("256w4", (300, 264, 192), True), ("skinnydma", (16, 1100, 1032), True),
                                                   ("skinnydma", (40, 1100, 1032), True), ("skinny", (16, 1100, 1032), True)])
