@@ -223,11 +223,14 @@ __global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
   const bool ragged_k = (K % BK) != 0;                  // only the last step can be partial
   constexpr int NKK = BK / 16;
   static_assert(NKK == 4, "the schedule below is written for four k slices per stage");
-  // This group's K steps: kt_begin .. kt_end-1 (all of them when KS == 1); every group runs the
-  // loop KTG times so that all wavefronts meet at the same barriers, idle once its steps are done.
+  // This group's K steps: kg, kg + KS, kg + 2 KS, ... (all of them when KS == 1), so that at any
+  // time the groups of a workgroup read neighbouring pieces of the same operand rows (with the
+  // operands stored k-contiguous: KS x 128 contiguous bytes of every row instead of KS pieces far
+  // apart); every group runs the loop KTG times so that all wavefronts meet at the same barriers,
+  // idle once its steps are done.
   const int KTG = (KT + KS - 1) / KS;
-  const int kt_begin = kg * KTG;
-  const int kt_end = kt_begin + KTG < KT ? kt_begin + KTG : KT;
+  const int kt_begin = kg;
+  const int kt_end = KT;
   auto load_tile = [&](int t) { load_global(t * BK, ragged_k && t == KT - 1); };
 
   // Software pipeline. Stage s holds the group's i-th tile (s = i & 1). During step kt:
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
   if (any) {
     load_tile(kt_begin);
     store_lds(0);
-    if (kt_begin + 1 < kt_end) load_tile(kt_begin + 1);
+    if (kt_begin + KS < kt_end) load_tile(kt_begin + KS);
   }
   __syncthreads();
 
@@ -260,12 +263,12 @@ __global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
   };
 
   for (int it = 0; it < KTG; ++it) {
-    const int kt = kt_begin + it;
+    const int kt = kt_begin + it * KS;
     const bool active = KS == 1 || kt < kt_end;
     const int cur = it & 1;
     const char* st = smem + cur * Cfg::STAGE;
     const char* nx = smem + (cur ^ 1) * Cfg::STAGE;
-    const bool have_next = kt + 1 < kt_end;
+    const bool have_next = kt + KS < kt_end;
 
     if (active) {
       load_frags(st, 1, af[1], bf[1]);
@@ -279,7 +282,7 @@ __global__ __launch_bounds__(WM* WN * 64 * KS) void gemm_tile_kernel(
       __builtin_amdgcn_sched_barrier(0);
       if (have_next) {
         store_lds(cur ^ 1);
-        if (kt + 2 < kt_end) load_tile(kt + 2);
+        if (kt + 2 * KS < kt_end) load_tile(kt + 2 * KS);
       }
       __builtin_amdgcn_sched_barrier(0);
 
@@ -555,7 +558,7 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   DeviceInfo di;
   const int64_t NCU = device_info(di) && di.ncu > 0 ? di.ncu : 256;
   const int64_t KT = (g.K + 63) / 64;
-  auto cost = [&](int64_t bm, int64_t bn, int64_t t_step, int64_t fixed, int parts) {
+  auto cost = [&](int64_t bm, int64_t bn, int64_t t_step, int64_t fixed, int parts, int kgroups) {
     const int64_t wgs = ((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * parts;
     const int64_t rounds = (wgs + NCU - 1) / NCU;
     const int64_t steps = (KT + parts - 1) / parts;
@@ -566,19 +569,29 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     // of 512: 32 x 28672 x 8192 measured 104-108 us on 64 x 64 tiles against 82 on 224 of 64 x 128)
     const int64_t base = (g.M + g.N) * g.K * 2 / 5200;
     const int64_t need = 6 * NCU / 10;
-    const int64_t arrive = wgs >= NCU ? base * rounds * NCU / wgs : (wgs >= need ? base : base * need / wgs);
+    // B stored N x K: a workgroup reads (K groups) x 128 contiguous bytes of each row at a time.
+    // The two-group tiles (256-byte pieces) need a workgroup on every CU and a little more to
+    // draw the full rate (64 x 28672 x 8192 on 224 tiles of 64 x 128: 107 us = 1.18 x the 5.2 TB/s
+    // time); the four-group 64 x 64 tile with between one and two workgroups per CU has them all
+    // resident at once, so there is no second round with idle CUs (the same problem on 448 such
+    // tiles: 102 us; 32 x 28672 x 8192: 95 against 105; 48 x ...: 95 against 100)
+    const int64_t need_here = g.transB && kgroups == 2 && parts == 1 ? NCU + NCU / 20 : need;
+    int64_t arrive = wgs >= NCU && wgs >= need_here ? base * rounds * NCU / wgs
+                     : (wgs >= need_here ? base : base * need_here / wgs);
+    if (g.transB && kgroups == 4 && parts == 1 && wgs > NCU && wgs <= 2 * NCU) arrive = base + base / 20;
     return (compute > arrive ? compute : arrive) + (parts > 1 ? 4000 + 2 * parts * g.M * g.N / 1000 : 0);
   };
-  // Among the candidates within 8 % of the best estimate the largest tile wins, then the fewest
-  // parts (a larger tile re-reads its operands from L2 less often, which the estimate leaves out:
-  // 64 x 8192 x 28672 measured 90 us on 64x128 tiles in four parts, 100 us on 64x64 tiles in two).
+  // Among the candidates within 8 % of the best estimate the largest tile wins (a larger tile
+  // re-reads its operands from L2 less often, which the estimate leaves out: 64 x 8192 x 28672
+  // measured 90 us on 64x128 tiles in four parts, 100-110 us on 64x64 tiles in two); for one tile
+  // size, the fewer parts unless more parts are estimated more than 5 % faster.
   const bool pp = gemm_pp_ok(g);
   // t: ns per K step of 64; fixed: ns per round before the first and after the last step, where a
   // fit over K gave one (2048 x 2048 x K on the split 128 x 128 kernel: 0.56 us per step + 2 us)
-  struct Cand { int variant; int bm, bn; int64_t t, fixed; };
-  const Cand big = {pp ? GEMM_256_PP16 : GEMM_256_W8, 256, 256, pp ? 1170 : 1800, 0};
-  const Cand split[] = {{GEMM_128_K2, 128, 128, 560, 2000}, {GEMM_64X128_K2, 64, 128, 370, 0}, {GEMM_64_K4, 64, 64, 220, 0}};
-  const Cand whole[] = {{GEMM_128_W8, 128, 128, 600, 0}, {GEMM_64X128_W8, 64, 128, 410, 0}, {GEMM_64_W4, 64, 64, 350, 0}};
+  struct Cand { int variant; int bm, bn; int64_t t, fixed; int kgroups; };
+  const Cand big = {pp ? GEMM_256_PP16 : GEMM_256_W8, 256, 256, pp ? 1170 : 1800, 0, 1};
+  const Cand split[] = {{GEMM_128_K2, 128, 128, 560, 2000, 2}, {GEMM_64X128_K2, 64, 128, 370, 0, 2}, {GEMM_64_K4, 64, 64, 220, 0, 4}};
+  const Cand whole[] = {{GEMM_128_W8, 128, 128, 600, 0, 1}, {GEMM_64X128_W8, 64, 128, 410, 0, 1}, {GEMM_64_W4, 64, 64, 350, 0, 1}};
   struct Choice { int variant, parts, area; int64_t t; };
   Choice all[20];
   int n_all = 0;
@@ -586,7 +599,7 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   auto fits = [&](int bm, int bn) {
     return !(bm > 64 && bm > (g.M + 63) / 64 * 64) && !(bn > 64 && bn > (g.N + 63) / 64 * 64);
   };
-  if (g.forced_parts <= 1 && fits(256, 256)) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 0, 1)};
+  if (g.forced_parts <= 1 && fits(256, 256)) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 0, 1, 1)};
   // The two-group kernel on 128 x 128 tiles, no K split across workgroups, in its two forms (fits
   // over K at 256 and 512 tiles, kernel time without the call):
   //   K steps of 64, two workgroups per CU: 0.84 us per step for a pair of tiles + 1.9 us per pair,
@@ -618,19 +631,24 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     if (parts > 1 && g.scratch_limit >= 0 && (int64_t)parts * g.M * g.N * 4 > g.scratch_limit) break;
     for (const auto& c : KT / parts >= 8 ? split : whole) {
       if (!fits(c.bm, c.bn)) continue;
-      all[n_all++] = Choice{c.variant, parts, c.bm * c.bn, cost(c.bm, c.bn, c.t, c.fixed, parts)};
+      all[n_all++] = Choice{c.variant, parts, c.bm * c.bn, cost(c.bm, c.bn, c.t, c.fixed, parts, c.kgroups)};
     }
   }
-  if (n_all == 0) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 0, 1)};
+  if (n_all == 0) all[n_all++] = Choice{big.variant, 1, 256 * 256, cost(256, 256, big.t, 0, 1, 1)};
   int64_t best = all[0].t;
   for (int i = 1; i < n_all; ++i) best = all[i].t < best ? all[i].t : best;
   Choice pick = all[0];
   bool have = false;
   for (int i = 0; i < n_all; ++i) {
     if (all[i].t > best + best / 12) continue;
-    if (!have || all[i].area > pick.area || (all[i].area == pick.area && all[i].parts < pick.parts) ||
-        (all[i].area == pick.area && all[i].parts == pick.parts && all[i].t < pick.t))
-      pick = all[i];
+    bool better = !have || all[i].area > pick.area;
+    if (have && all[i].area == pick.area) {
+      // same tile: the fewer parts, unless more parts are estimated more than 5 % faster
+      if (all[i].parts == pick.parts) better = all[i].t < pick.t;
+      else if (all[i].parts < pick.parts) better = all[i].t <= pick.t + pick.t / 20;
+      else better = all[i].t + all[i].t / 20 < pick.t;
+    }
+    if (better) pick = all[i];
     have = true;
   }
   int v = pick.variant;
