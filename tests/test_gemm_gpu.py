@@ -382,6 +382,37 @@ def test_accumulate_into_fp32_c(variant, transB, dtype):
     assert np.all(err <= bound), "worst err/bound %.3f" % float(np.max(err / bound))
 
 
+@pytest.mark.parametrize("transB", [False, True])
+def test_k_steps_of_128_fp32_accumulate_and_fused_epilogue(transB):
+    """The 128 x 128 two-group kernel with K steps of 128 through the other two epilogues: fp32
+    C += A*B (twice) and act(A*B + bias)."""
+    import oracle
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    M, N, K = 392, 520, 384
+    try:
+        binding.mlt_diag_force_variant(gemm="128pp16k128")
+        for dtype in (BF16, FP16):
+            A, B = inputs.gemm_inputs(M, N, K, dtype, 31, transB=transB)
+            At, Bt = inputs.bits_to_torch(A, dtype, dev), inputs.bits_to_torch(B, dtype, dev)
+            C0 = np.random.default_rng(32).standard_normal((M, N)).astype(np.float32)
+            Ct = torch.from_numpy(C0.copy()).to(dev)
+            binding.mlt_gemm_acc(At, Bt, Ct, transB=transB)
+            binding.mlt_gemm_acc(At, Bt, Ct, transB=transB)
+            torch.cuda.synchronize()
+            assert binding.mlt_last_kernel().endswith("128x128x128_w2x4_pp16")
+            Cref, T = oracle.gemm(A, B, dtype, transB=transB)
+            err = np.abs(Ct.double().cpu().numpy() - (C0.astype(np.float64) + 2.0 * Cref))
+            bound = 2.0 * (K * 2.0 ** -24) * T + 2.0 ** -22 * (np.abs(C0) + 2.0 * T) + 1e-6
+            assert np.all(err <= bound), "worst err/bound %.3f" % float(np.max(err / bound))
+            for act in (0, 1, 2):
+                bias = inputs.bias_input(N, dtype, 33, std=4.0)
+                pu.run_check_gemm_bias_act(A, B, bias, act, dtype, transB=transB)
+                assert binding.mlt_last_kernel().endswith("128x128x128_w2x4_pp16")
+    finally:
+        binding.mlt_diag_force_variant(gemm="auto")
+
+
 def test_accumulate_edge_cases():
     from paper_2503_14985_amd import binding
     dev = torch.device("cuda:0")
