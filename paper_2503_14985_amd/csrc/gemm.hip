@@ -619,7 +619,10 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     const int64_t pairs = wgs / (2 * NCU), rem = wgs - pairs * 2 * NCU;
     const int64_t own64 = pairs * (KT * 840 + 1900) +
                           (rem > NCU ? KT * 840 + 1900 : rem > 0 ? KT * 519 + 4000 : 0);
-    all[n_all++] = Choice{GEMM_128_PP16, 1, 128 * 128, own64 > arrive ? own64 : arrive};
+    // (with at most one tile per CU and K a multiple of 128 the 128-deep form is never slower, also
+    // where both are bound by operand arrival: 128 x 28672 x 8192 116 against 134 us)
+    if (wgs > NCU || g.K % 128 != 0)
+      all[n_all++] = Choice{GEMM_128_PP16, 1, 128 * 128, own64 > arrive ? own64 : arrive};
     if (g.K % 128 == 0) {
       const int64_t own128 = ((wgs + NCU - 1) / NCU) * (KT * 436 + 4300);
       all[n_all++] = Choice{GEMM_128_PP16_K128, 1, 128 * 128, own128 > arrive ? own128 : arrive};
