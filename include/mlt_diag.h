@@ -76,8 +76,8 @@ int mlt_query_tiling(int op, const int64_t dims[4], int dtype, int32_t out[10]);
  * process, for tuning and for tests that have to reach every kernel. A NULL argument leaves that
  * choice as it is; "" or "auto" restores the automatic choice. A forced kernel that cannot take a
  * problem (alignment, shape) falls back to one that can, as the automatic choice would.
- *   gemm_variant  "general", "256", "256w8", "256pp16", "256w4", "256w8x1", "256w1x8", "128w8",
- *                 "64x128", "64", "128k2", "64x128k2", "64k4", "skinny", "skinnydma"
+ *   gemm_variant  "general", "256", "256w8", "256pp16", "128pp16", "128pp16k128", "256w4", "256w8x1",
+ *                 "256w1x8", "128w8", "64x128", "64", "128k2", "64x128k2", "64k4", "skinny", "skinnydma"
  *   mha_variant   "pp32", "pp16", "ps"
  * The initial values come from the environment variables MLT_GEMM_VARIANT and MLT_MHA_VARIANT,
  * which are read once, at the first call that needs them. Not synchronised with compute calls
