@@ -23,7 +23,9 @@
  *     with hipMalloc at the first call that needs it, grown by doubling from 4 MiB (16 MiB covers
  *     every split the library chooses by itself) and kept until the process ends. Calls on one
  *     stream are ordered by the stream; calls on different streams use different buffers. If the
- *     allocation fails the call runs without the split. mlt_gemm_noalloc never allocates.
+ *     allocation fails, or the stream is recording into a graph and has no buffer yet, the call
+ *     runs without the split (same result up to summation order). mlt_gemm_noalloc never
+ *     allocates.
  */
 #ifndef MLT_H_
 #define MLT_H_

@@ -786,6 +786,13 @@ std::mutex g_scratch_mu;
 
 }  // namespace
 
+// true while `s` records into a graph: nothing may be allocated then
+static bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return st != hipStreamCaptureStatusNone;
+}
+
 float* cached_scratch(int64_t bytes, hipStream_t s) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
@@ -799,6 +806,10 @@ float* cached_scratch(int64_t bytes, hipStream_t s) {
     slot = &g_scratch[g_scratch_used];
     *slot = ScratchSlot{dev, s, nullptr, 0};
   }
+  // a buffer that is there is used under capture as well; a new one is not allocated in the
+  // middle of a capture (the call then runs without the split; mlt_gemm_noalloc is the entry point
+  // made for captured code)
+  if (stream_is_capturing(s)) return nullptr;
   int64_t want = slot->bytes > 0 ? 2 * slot->bytes : (int64_t)4 << 20;
   while (want < bytes) want *= 2;
   void* p = nullptr;
@@ -834,7 +845,7 @@ float* static_scratch_of_current_device() {
   return g_static_scratch[dev];
 }
 
-int run_gemm(const GemmArgs& g_in, const GemmPlan& p, hipStream_t s) {
+int run_gemm(const GemmArgs& g_in, GemmPlan& p, hipStream_t s) {
   GemmArgs g = g_in;
   g.parts = p.parts;
   bool own = false;
@@ -842,12 +853,14 @@ int run_gemm(const GemmArgs& g_in, const GemmPlan& p, hipStream_t s) {
     g.scratch = cached_scratch(p.scratch_bytes, s);
     if (!g.scratch) {
       void* ws = nullptr;
-      if (hipMallocAsync(&ws, (size_t)p.scratch_bytes, s) == hipSuccess && ws) {
+      if (!stream_is_capturing(s) && hipMallocAsync(&ws, (size_t)p.scratch_bytes, s) == hipSuccess && ws) {
         g.scratch = static_cast<float*>(ws);
         own = true;
       } else {
         (void)hipGetLastError();
         g.parts = 1;
+        p.parts = 1;                                       // what ran, for the reported kernel name
+        p.scratch_bytes = 0;
       }
     }
   }

@@ -63,7 +63,7 @@ constexpr int64_t kStaticScratchBytes = (int64_t)32 << 20;
 float* static_scratch_of_current_device();
 
 GemmPlan plan_gemm(const GemmArgs& g);
-int run_gemm(const GemmArgs& g, const GemmPlan& p, hipStream_t s);
+int run_gemm(const GemmArgs& g, GemmPlan& p, hipStream_t s);
 bool gemm_pp_ok(const GemmArgs& g);            // gemm_pp.hip: can the two-group kernel take this problem?
 int run_gemm_pp(const GemmArgs& g, int tile, int kstep, hipStream_t s);   // tile: 256 or 128; K step 64 or (tile 128 only) 128
 int run_gemm_w4(const GemmArgs& g, hipStream_t s);   // gemm_w4.hip; same operand requirements (gemm_pp_ok)

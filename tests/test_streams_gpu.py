@@ -115,3 +115,29 @@ def test_captured_step_replays_to_the_eager_result():
         _run(binding, other, scratch)
         torch.cuda.synchronize()
         assert _same(static, eager), "replay %d differs from the eager result" % rep
+
+
+def test_capture_on_a_stream_without_scratch_does_not_allocate():
+    """A GEMM that would split K across workgroups, captured on a stream the library has no scratch
+    buffer for: the call must not allocate in the middle of the capture; it runs without the split
+    (the kernel name says so) and the replays meet the oracle bound."""
+    from paper_2503_14985_amd import binding
+    dev = torch.device("cuda:0")
+    M, N, K = 64, 2048, 64 * 160
+    A_h, B_h = inputs.gemm_inputs(M, N, K, BF16, 9, transB=True, std=0.02)
+    A, B = inputs.bits_to_torch(A_h, BF16, dev), inputs.bits_to_torch(B_h, BF16, dev)
+    eager = binding.mlt_gemm(A, B, transB=True)
+    assert "splitk" in binding.mlt_last_kernel()
+    torch.cuda.synchronize()
+    static = torch.empty_like(eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):                   # records on a fresh side stream
+        binding.mlt_gemm(A, B, C=static, transB=True)
+        captured_name = binding.mlt_last_kernel()
+    assert "splitk" not in captured_name, captured_name
+    for rep in range(3):
+        static.fill_(0)
+        graph.replay()
+        binding.mlt_gemm(A, B, transB=True)          # eager work between the replays
+        torch.cuda.synchronize()
+        pu.check_gemm(A_h, B_h, static, BF16, True, seed=9)
