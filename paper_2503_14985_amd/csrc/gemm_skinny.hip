@@ -67,7 +67,7 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_nt_kernel(
       const int k = (c0 + u * SK_NW) * 32 + 8 * q;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
-        bfrag[u][nt] = *reinterpret_cast<const u32x4_mem*>(bp[nt] + ((whole || k < K) ? k : 0));
+        bfrag[u][nt] = load_stream16(bp[nt] + ((whole || k < K) ? k : 0));   // B is read once
     }
     __builtin_amdgcn_sched_barrier(0);                     // all B loads of the batch go out first
 #pragma unroll
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(SK_NT) void gemm_skinny_dma_kernel(
         const int nrow = n0 + r < N ? r : N - 1 - n0;      // clamped: such columns are never stored
         int ck = (lane % L::LPR) ^ (r & 15);               // the 16-byte chunk this lane fetches
         if (k0 + ck * 8 >= K) ck = 0;                      // past K (last stage): any valid chunk, zeroed later
-        load_lds16(Bw, (uint32_t)nrow * (uint32_t)ldb * 2u + (uint32_t)(k0 + ck * 8) * 2u,
+        load_lds16_stream(Bw, (uint32_t)nrow * (uint32_t)ldb * 2u + (uint32_t)(k0 + ck * 8) * 2u,
                       slot + (uint32_t)ii * 1024u);
       }
       ++i_g;

@@ -111,8 +111,8 @@ __global__ __launch_bounds__(PG_NT) void paged_decode_kernel(
     const int64_t base = unit_base(u) + lane_off;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      kf[i] = *reinterpret_cast<const u32x4_mem*>(Kc + base + i * RPI * D);
-      vf[i] = *reinterpret_cast<const u32x4_mem*>(Vc + base + i * RPI * D);
+      kf[i] = load_stream16(Kc + base + i * RPI * D);     // the cache is read once: streaming loads
+      vf[i] = load_stream16(Vc + base + i * RPI * D);
     }
   };
 
