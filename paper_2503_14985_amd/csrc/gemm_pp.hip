@@ -148,11 +148,18 @@ __global__ __launch_bounds__(PP_NT, (BT == 128 && BK == 64) ? 4 : 1) void gemm_p
   const int KT = K / PP_BK;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;      // LDS byte address of the buffer
   // this wavefront's NL blocks of operand tile t (A_t for group 1, B_t for group 0) into a slot
+  // (an operand that only one row or column of tiles reads is read exactly once: streaming form)
+  const bool stream = grp == 1 ? nbn == 1 : nbm == 1;
   auto issue_loads = [&](int t, int slot) {
     const char* gp = ld_base + (int64_t)t * ld_kstep;
     const uint32_t dst = lds0 + slot * PP_SLOT + (wave & 3) * (NL * 1024);
+    if (stream) {
 #pragma unroll
-    for (int i = 0; i < NL; ++i) load_lds16(gp, voff[i], dst + i * 1024);
+      for (int i = 0; i < NL; ++i) load_lds16_stream(gp, voff[i], dst + i * 1024);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) load_lds16(gp, voff[i], dst + i * 1024);
+    }
   };
   // ---- fragment addresses inside a stage (per lane; tile and k slice offsets are immediates)
   // MS = 32: MFMA 32x32x16, 4 k slices of 16 per K step, A tiles of 32 rows, B tiles of 32 columns.
