@@ -659,13 +659,15 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   // ---- the skinny kernels (B stored N x K, no LDS staging of A): the automatic choice for one
   // 16-row tile of A, and for two when they beat the tile kernels' estimate; B streamed through
   // an LDS ring (16 columns x 512 k per stage, the A fragments of a k stage shared by a group of
-  // column blocks) once B is well beyond the caches: measured 5.4 TB/s of B for M <= 16 and
-  // 3.9 TB/s for two row tiles (32 x 8192 x 28672: 125 us, against 91 us for the tile kernels with
-  // K split four ways). Taller A goes to the tile kernels, which stage A through LDS once per
-  // tile (64 x 28672 x 8192: 92-103 us against 177 us streaming; 64 x 14336 x 4096: 20 us against
-  // 43 us).
+  // column blocks) once B is well beyond the caches: measured 5.7 TB/s of B for M <= 16; for two
+  // row tiles 5.1-5.9 TB/s with 16384 columns or more (32 x 28672 x 8192: 91 us against 97 us for
+  // the tile kernels) and 3.0-4.6 TB/s with fewer (32 x 8192 x 28672: 103 us, against 85 us for
+  // the tile kernels with K split four ways). Taller A goes to the tile kernels, which stage A
+  // through LDS once per tile (64 x 28672 x 8192: 99 us against 160 us streaming; 64 x 14336 x
+  // 4096: 20 us against 43 us).
   const bool big_b = g.N * g.K >= ((int64_t)1 << 25);
-  const bool stream_wins = g.M <= 16 || g.N * g.K * 2 / 3900 < best;
+  const int64_t two_tile_rate = g.N >= 16384 ? 5000 : 3900;  // bytes of B per us
+  const bool stream_wins = g.M <= 16 || g.N * g.K * 2 / two_tile_rate < best;
   const bool skinny_auto = g.forced == GEMM_AUTO && g.M <= 32 && (!big_b || stream_wins);
   if ((g.forced == GEMM_SKINNY_DMA || (skinny_auto && big_b)) && gemm_skinny_dma_ok(g)) {
     p.variant = GEMM_SKINNY_DMA;
