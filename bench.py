@@ -4,7 +4,7 @@ fp32 accumulate) followed by one non-causal bf16 attention forward B4 H32 S4096 
 the C ABI. Prints one JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W]
-  python bench.py --sweep gemm [--torch] [--sweep-dtype fp16]   markdown table over the GEMM shape families
+  python bench.py --sweep gemm [--torch] [--cold] [--sweep-dtype fp16]   markdown table over the GEMM shape families
   python bench.py --sweep fa2                                    markdown table over the paper's FlashAttention-2 sweep
 
 `value` is the whole step's TFLOP/s (2*M*N*K + 4*B*H*Sq*Sk*D flop per step) with all inputs
@@ -372,6 +372,7 @@ GEMM_SWEEP_SHAPES = [
     (512, 8192, 8192, True), (256, 8192, 8192, True), (256, 14336, 4096, True), (512, 4096, 14336, True),
     (64, 4096, 4096, True), (64, 14336, 4096, True), (64, 28672, 8192, True), (64, 8192, 28672, True),
     (64, 131072, 4096, True), (32, 28672, 8192, True), (32, 8192, 28672, True),
+    (32, 16384, 8192, True), (32, 32768, 4096, True), (32, 65536, 2048, True),
     (16, 4096, 4096, True), (16, 28672, 8192, True), (16, 8192, 28672, True), (16, 131072, 4096, True),
     (16, 4096, 4096, False), (32, 28672, 8192, False), (1, 28672, 8192, True),
 ]
@@ -390,14 +391,19 @@ def _time_back_to_back(torch, fn, n):
     return e0.elapsed_time(e1) / n
 
 
-def sweep_gemm(torch, binding, dev, with_torch, dt):
+def sweep_gemm(torch, binding, dev, with_torch, dt, with_cold=False):
     """Markdown table of mlt_gemm over the shape families. Each shape is launched back to back
     (best of two runs of n launches; the library launches on torch's current stream here, so
     torch's events see it) on torch.randn inputs: N(0,1) for the square shapes, N(0, 0.02^2) for
-    the shapes with B stored N x K. Times below about 12 us are bounded by the Python call."""
+    the shapes with B stored N x K. Times below about 12 us are bounded by the Python call.
+    with_cold: the decode shapes (M <= 64, B stored N x K) once more with B rotating over copies
+    of more than 800 MB in total, so that no launch finds B in the 256 MiB last-level cache, as
+    in a decoder, where every weight matrix is read once per token."""
     head = "| M x N x K | B stored | kernel | us | TFLOP/s | GB/s (A+B+C once) |"
-    print(head + (" torch us |" if with_torch else ""))
-    print("|---|---|---|---|---|---|" + ("---|" if with_torch else ""))
+    print(head + (" torch us |" if with_torch else "") +
+          ((" cold B: us |" + (" torch us |" if with_torch else "")) if with_cold else ""))
+    print("|---|---|---|---|---|---|" + ("---|" if with_torch else "") +
+          (("---|" + ("---|" if with_torch else "")) if with_cold else ""))
     for (M, N, K, tb) in GEMM_SWEEP_SHAPES:
         std = 0.02 if (tb or M <= 64) else 1.0
         A = (torch.randn(M, K, device=dev, dtype=torch.float32) * std).to(dt)
@@ -412,6 +418,27 @@ def sweep_gemm(torch, binding, dev, with_torch, dt):
             tms = min(_time_back_to_back(torch, lambda: torch.matmul(A, B.t() if tb else B, out=C), n)
                       for _ in range(2))
             line += " %.1f |" % (tms * 1e3)
+        if with_cold:
+            if M <= 64 and tb:
+                copies = [B] + [(torch.randn((N, K), device=dev, dtype=torch.float32) * std).to(dt)
+                                for _ in range(max(1, int(800e6 // (N * K * 2))))]
+                turn = [0]
+
+                def rotating(f):
+                    def call():
+                        turn[0] += 1
+                        f(copies[turn[0] % len(copies)])
+                    return call
+                cms = min(_time_back_to_back(
+                    torch, rotating(lambda b: binding.mlt_gemm(A, b, C=C, transB=True)), n) for _ in range(2))
+                line += " %.1f |" % (cms * 1e3)
+                if with_torch:
+                    ctms = min(_time_back_to_back(
+                        torch, rotating(lambda b: torch.matmul(A, b.t(), out=C)), n) for _ in range(2))
+                    line += " %.1f |" % (ctms * 1e3)
+                del copies
+            else:
+                line += " |" + (" |" if with_torch else "")
         print(line, flush=True)
 
 
@@ -489,6 +516,8 @@ def main():
                          "FlashAttention-2 sweep (Section 4.2)")
     ap.add_argument("--torch", action="store_true", help="--sweep gemm: add torch.matmul on the same tensors")
     ap.add_argument("--sweep-dtype", choices=["bf16", "fp16"], default="bf16", help="--sweep gemm: element type")
+    ap.add_argument("--cold", action="store_true",
+                    help="--sweep gemm: time the decode shapes once more with B rotating over more than the last-level cache holds")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (kernels on one GPU's share of the "
@@ -512,7 +541,7 @@ def main():
         torch.manual_seed(0)
         if args.sweep == "gemm":
             sweep_gemm(torch, binding, dev, args.torch,
-                       torch.bfloat16 if args.sweep_dtype == "bf16" else torch.float16)
+                       torch.bfloat16 if args.sweep_dtype == "bf16" else torch.float16, args.cold)
         else:
             sweep_fa2(torch, binding, dev)
         return

@@ -660,13 +660,18 @@ GemmPlan plan_gemm(const GemmArgs& g) {
   // 16-row tile of A, and for two when they beat the tile kernels' estimate; B streamed through
   // an LDS ring (16 columns x 512 k per stage, the A fragments of a k stage shared by a group of
   // column blocks) once B is well beyond the caches: measured 5.7 TB/s of B for M <= 16; for two
-  // row tiles 5.1-5.9 TB/s with 16384 columns or more (32 x 28672 x 8192: 91 us against 97 us for
-  // the tile kernels) and 3.0-4.6 TB/s with fewer (32 x 8192 x 28672: 103 us, against 85 us for
-  // the tile kernels with K split four ways). Taller A goes to the tile kernels, which stage A
-  // through LDS once per tile (64 x 28672 x 8192: 99 us against 160 us streaming; 64 x 14336 x
-  // 4096: 20 us against 43 us).
+  // row tiles 4.7-5.9 TB/s with 16384 columns or more and 3.0-4.6 TB/s with fewer (32 x 8192 x
+  // 28672: 103 us, against 85 us for the tile kernels with K split four ways). The rates that
+  // decide are those with B coming from memory, as the weights of a decoder do (every matrix is
+  // read once per token, and a model is far larger than the 256 MiB last-level cache): the
+  // streaming kernel's non-temporal loads make it indifferent to what that cache holds, while the
+  // tile kernels run up to 40 % faster when the same B of less than 256 MB is multiplied again
+  // and again (32 x 16384 x 8192: tile kernels 41 us on a repeated B and 59 us on rotating ones,
+  // the streaming kernel 55 and 56 us; 32 x 65536 x 2048: 43 / 65 against 53 / 54 us). Taller A
+  // goes to the tile kernels, which stage A through LDS once per tile (64 x 28672 x 8192: 99 us
+  // against 160 us streaming; 64 x 14336 x 4096: 20 us against 43 us).
   const bool big_b = g.N * g.K >= ((int64_t)1 << 25);
-  const int64_t two_tile_rate = g.N >= 16384 ? 5000 : 3900;  // bytes of B per us
+  const int64_t two_tile_rate = g.N >= 16384 ? 5600 : 3900;  // bytes of B per us, B from memory
   const bool stream_wins = g.M <= 16 || g.N * g.K * 2 / two_tile_rate < best;
   const bool skinny_auto = g.forced == GEMM_AUTO && g.M <= 32 && (!big_b || stream_wins);
   if ((g.forced == GEMM_SKINNY_DMA || (skinny_auto && big_b)) && gemm_skinny_dma_ok(g)) {
