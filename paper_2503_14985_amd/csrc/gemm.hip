@@ -568,7 +568,10 @@ GemmPlan plan_gemm(const GemmArgs& g) {
     // beyond one workgroup per CU the last round's idle CUs count (448 workgroups take the time
     // of 512: 32 x 28672 x 8192 measured 104-108 us on 64 x 64 tiles against 82 on 224 of 64 x 128)
     const int64_t base = (g.M + g.N) * g.K * 2 / 5200;
-    const int64_t need = 6 * NCU / 10;
+    // (the decode shapes are priced with B coming from memory: then fewer workgroups than CUs do
+    // not keep enough bytes in flight; 64 x 8192 x 8192 on 128 tiles of 64 x 64: 43 us with B
+    // rotating over more than the last-level cache holds, 34-37 us with K split two or four ways)
+    const int64_t need = g.M <= 64 && g.transB ? NCU : 6 * NCU / 10;
     // B stored N x K: a workgroup reads (K groups) x 128 contiguous bytes of each row at a time.
     // The two-group tiles (256-byte pieces) need a workgroup on every CU and a little more to
     // draw the full rate (64 x 28672 x 8192 on 224 tiles of 64 x 128: 107 us = 1.18 x the 5.2 TB/s
